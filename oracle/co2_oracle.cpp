@@ -1,0 +1,322 @@
+// CO2 outer-update oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+//
+// A plain, slow, single-threaded CPU statement of what one CO2 worker computes
+// once its tau local steps have finished (CO2 paper, Algorithm 1, the three
+// update lines after the wait on the previous asynchronous all-reduce;
+// Definition 3.1 / Eq. 3 for the staleness gap; Section 3.3 for Clip), plus the
+// base optimizer's local update (Algorithm 1, "LU" line, with AdamW as the base
+// optimizer, Section 4.1).  Only tests, the smoke check and the bench's CPU
+// baseline may call it.  It shares no code, header, table or helper with the
+// HIP library and is compiled by g++ with -O2 -ffp-contract=off so that every
+// fp32 product and sum below is rounded once, as written.
+//
+// Two evaluations are given for every update:
+//   *_f32 : the arithmetic type of the device path (fp32 elementwise work,
+//           fp64 for the two norms and the per-segment scalar Lambda);
+//   *_f64 : everything in fp64 ("truth"), used to bound the fp32 evaluation's
+//           own rounding error.
+//
+// Readings taken where the paper is silent (each is also listed in the design
+// document):
+//   * ||.|| in Eq. 3 is the L2 norm over one parameter tensor ("segment"),
+//     and Lambda is broadcast over that tensor's coordinates.  S = n gives the
+//     per-coordinate reading, S = 1 the global one.
+//   * Numerator ||x_{t,0} - x_{t-1,0}||: by Algorithm 1's last line one round
+//     earlier this difference is -alpha*Clip(m_{t-1}, phi), so it is formed as
+//     alpha * ||Clip(m_{t-1}, phi)|| from the momentum *before* its update.
+//   * Denominator tau*||x_{t-1,1} - x_{t-1,0}||: the per-segment first-inner-
+//     step norms are an input (first_step_norm); when absent, the norm of the
+//     worker's own previous pseudo-gradient (deltas[0]) stands for the whole
+//     product tau*||first step||.
+//   * A coefficient c scales the ratio: Lambda = c*ratio + 1 (c = 1 is the
+//     paper, c = 0 is its "w/o penalty" ablation).  A zero denominator gives
+//     Lambda = 1.
+//   * Outer round t = 0 performs no momentum/iterate update (Section 3.1,
+//     "special case of first outer iteration"): x_{1,0} = x_{0,0}, m stays 0.
+//
+// parity pins: tests/test_oracle_*.py (hand-expanded example, closed forms,
+// invariants, library AdamW).  Nothing here is "parity unpinned".
+
+#include <cmath>
+#include <cstddef>
+#include <cstdint>
+
+namespace {
+
+// Section 3.3: Clip(chi, phi) = max{-phi, min{chi, phi}}, coordinate-wise.
+template <typename T>
+inline T clip_coord(T chi, T phi) {
+  T lo = (chi < phi) ? chi : phi;      // min{chi, phi}
+  return (lo > -phi) ? lo : -phi;      // max{-phi, .}
+}
+
+inline int check_table(int64_t n, int32_t S, const int64_t* seg_off) {
+  if (n < 0 || S < 1 || seg_off == nullptr) return -1;
+  if (seg_off[0] != 0 || seg_off[S] != n) return -1;
+  for (int32_t s = 0; s < S; ++s)
+    if (seg_off[s + 1] < seg_off[s]) return -1;
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Per-segment sum of squares of one buffer, fp64 accumulation in ascending
+// index order (the quantity under the root of either norm in Eq. 3).
+// If phi > 0 the value is clipped coordinate-wise in fp32 first.
+int co2_oracle_sqnorms(int64_t n, int32_t S, const int64_t* seg_off,
+                       const float* buf, float phi, double* out) {
+  if (check_table(n, S, seg_off) || !buf || !out) return -1;
+  for (int32_t s = 0; s < S; ++s) {
+    double acc = 0.0;
+    for (int64_t j = seg_off[s]; j < seg_off[s + 1]; ++j) {
+      float v = buf[j];
+      if (phi > 0.0f) v = clip_coord<float>(v, phi);
+      double dv = static_cast<double>(v);
+      acc += dv * dv;
+    }
+    out[s] = acc;
+  }
+  return 0;
+}
+
+// One outer update, fp32-ordered evaluation.
+//
+//   x      in: x^{(i)}_{t,tau} (local params after the inner loop)
+//          out: x_{t+1,0}.  May be NULL ("split form": only m and the next
+//          anchor are produced; then dout must be NULL as well).
+//   a_in   x_{t,0}; a_out receives x_{t+1,0} (may be the same array as a_in).
+//   m      in: m_{t-1}; out: m_t.
+//   d      K arrays: round t-1's pseudo-gradients x_{t-1,0} - x^{(k)}_{t-1,tau}
+//          of the K workers (their mean is what the all-reduce delivers).
+//   dout   out: x_{t,0} - x^{(i)}_{t,tau}, this round's pseudo-gradient (the
+//          payload of the all-reduce launched now).
+//   first_step_norm  NULL, or S values ||x_{t-1,1} - x_{t-1,0}||_s.
+//   lambda_out, M2_out, T_out: optional S-vectors for inspection
+//          (Lambda, sum Clip(m_{t-1})^2, the denominator).
+//   nclipped: optional, number of coordinates with |m_t| > phi.
+int co2_oracle_outer_step_f32(int64_t n, int32_t S, const int64_t* seg_off,
+                              int32_t K, float alpha, float beta, float phi,
+                              float c, int32_t tau, int64_t step,
+                              float* x, const float* a_in, float* a_out,
+                              float* m, const float* const* d, float* dout,
+                              const float* first_step_norm,
+                              float* lambda_out, double* M2_out, double* T_out,
+                              int64_t* nclipped) {
+  if (check_table(n, S, seg_off) || !a_in || !a_out || !m) return -1;
+  if ((x == nullptr) != (dout == nullptr)) return -1;
+  if (K < 1 || tau < 1 || !(phi > 0.0f) || step < 0) return -1;
+  if (nclipped) *nclipped = 0;
+
+  if (step == 0) {
+    // First outer iteration: the AAR is launched, nothing else happens.
+    for (int64_t j = 0; j < n; ++j) {
+      float aj = a_in[j];
+      if (x) { dout[j] = aj - x[j]; x[j] = aj; }
+      a_out[j] = aj;
+    }
+    for (int32_t s = 0; s < S; ++s) {
+      if (lambda_out) lambda_out[s] = 1.0f;
+      if (M2_out) M2_out[s] = 0.0;
+      if (T_out) T_out[s] = 0.0;
+    }
+    return 0;
+  }
+  if (!d) return -1;
+  for (int32_t k = 0; k < K; ++k) if (!d[k]) return -1;
+
+  const float rK = static_cast<float>(1.0 / static_cast<double>(K));
+
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t lo = seg_off[s], hi = seg_off[s + 1];
+
+    // Eq. 3 numerator: ||x_{t,0} - x_{t-1,0}||_s = alpha*||Clip(m_{t-1},phi)||_s.
+    double M2 = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      double cm = static_cast<double>(clip_coord<float>(m[j], phi));
+      M2 += cm * cm;
+    }
+    // Eq. 3 denominator: tau*||x_{t-1,1} - x_{t-1,0}||_s.
+    double T;
+    if (first_step_norm) {
+      T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
+    } else {
+      double P2 = 0.0;
+      for (int64_t j = lo; j < hi; ++j) {
+        double dv = static_cast<double>(d[0][j]);
+        P2 += dv * dv;
+      }
+      T = std::sqrt(P2);
+    }
+    // Lambda_t = c * numerator / denominator + 1  (Algorithm 1, gap update).
+    double Lam = 1.0;
+    if (c != 0.0f && T != 0.0) {
+      Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * std::sqrt(M2) / T + 1.0;
+    }
+    const float inv = static_cast<float>(1.0 / Lam);
+    if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+    if (M2_out) M2_out[s] = M2;
+    if (T_out) T_out[s] = T;
+
+    for (int64_t j = lo; j < hi; ++j) {
+      const float aj = a_in[j];
+      // This round's local pseudo-gradient (what the new AAR carries).
+      if (x) dout[j] = aj - x[j];
+      // Mean of the K workers' round t-1 pseudo-gradients, left to right.
+      float sum = d[0][j];
+      for (int32_t k = 1; k < K; ++k) sum = sum + d[k][j];
+      const float dbar = sum * rK;
+      // m_t = beta*m_{t-1} + (1/Lambda_t)*(x_{t-1,0} - x_{t-1,tau}).
+      const float bm = beta * m[j];
+      const float pen = dbar * inv;
+      const float mt = bm + pen;
+      // x_{t+1,0} = x_{t,0} - alpha*Clip(m_t, phi).
+      const float cm = clip_coord<float>(mt, phi);
+      const float stepv = alpha * cm;
+      const float xn = aj - stepv;
+      if (nclipped && (mt > phi || mt < -phi)) ++*nclipped;
+      m[j] = mt;
+      if (x) x[j] = xn;
+      a_out[j] = xn;
+    }
+  }
+  return 0;
+}
+
+// The same update with every quantity in fp64.
+int co2_oracle_outer_step_f64(int64_t n, int32_t S, const int64_t* seg_off,
+                              int32_t K, double alpha, double beta, double phi,
+                              double c, int32_t tau, int64_t step,
+                              double* x, const double* a_in, double* a_out,
+                              double* m, const double* const* d, double* dout,
+                              const double* first_step_norm,
+                              double* lambda_out) {
+  if (check_table(n, S, seg_off) || !a_in || !a_out || !m) return -1;
+  if ((x == nullptr) != (dout == nullptr)) return -1;
+  if (K < 1 || tau < 1 || !(phi > 0.0) || step < 0) return -1;
+
+  if (step == 0) {
+    for (int64_t j = 0; j < n; ++j) {
+      double aj = a_in[j];
+      if (x) { dout[j] = aj - x[j]; x[j] = aj; }
+      a_out[j] = aj;
+    }
+    if (lambda_out) for (int32_t s = 0; s < S; ++s) lambda_out[s] = 1.0;
+    return 0;
+  }
+  if (!d) return -1;
+  for (int32_t k = 0; k < K; ++k) if (!d[k]) return -1;
+
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t lo = seg_off[s], hi = seg_off[s + 1];
+    double M2 = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      double cm = clip_coord<double>(m[j], phi);
+      M2 += cm * cm;
+    }
+    double T;
+    if (first_step_norm) {
+      T = static_cast<double>(tau) * first_step_norm[s];
+    } else {
+      double P2 = 0.0;
+      for (int64_t j = lo; j < hi; ++j) P2 += d[0][j] * d[0][j];
+      T = std::sqrt(P2);
+    }
+    double Lam = 1.0;
+    if (c != 0.0 && T != 0.0) Lam = c * alpha * std::sqrt(M2) / T + 1.0;
+    if (lambda_out) lambda_out[s] = Lam;
+
+    for (int64_t j = lo; j < hi; ++j) {
+      const double aj = a_in[j];
+      if (x) dout[j] = aj - x[j];
+      double sum = 0.0;
+      for (int32_t k = 0; k < K; ++k) sum += d[k][j];
+      const double dbar = sum / static_cast<double>(K);
+      const double mt = beta * m[j] + dbar / Lam;
+      const double xn = aj - alpha * clip_coord<double>(mt, phi);
+      m[j] = mt;
+      if (x) x[j] = xn;
+      a_out[j] = xn;
+    }
+  }
+  return 0;
+}
+
+// Local update with AdamW as the base optimizer (decoupled weight decay,
+// Loshchilov & Hutter): for inner step index k >= 1
+//   m1 <- b1*m1 + (1-b1)*g ;  v <- b2*v + (1-b2)*g*g
+//   p  <- p*(1 - lr*wd)
+//   p  <- p - (lr/(1-b1^k)) * m1 / (sqrt(v)/sqrt(1-b2^k) + eps)
+// Gradients arrive as bf16 bit patterns (widened exactly by a 16-bit shift).
+// Optional: dout = anchor - p_out (the pseudo-gradient taken at the last inner
+// step of a round) and, per segment, the sum of squares of p_out - p_in (whose
+// root at the first inner step is the ||x_{t,1} - x_{t,0}|| of Eq. 3).
+int co2_oracle_adamw_f32(int64_t n, const float* p_in, float* p_out,
+                         const uint16_t* grad_bf16, float* exp_avg,
+                         float* exp_avg_sq, float lr, float beta1, float beta2,
+                         float eps, float weight_decay, int64_t k,
+                         const float* anchor, float* dout,
+                         int32_t S, const int64_t* seg_off, double* step_sq_out) {
+  if (n < 0 || !p_in || !p_out || !grad_bf16 || !exp_avg || !exp_avg_sq || k < 1) return -1;
+  if ((anchor == nullptr) != (dout == nullptr)) return -1;
+  if (step_sq_out && check_table(n, S, seg_off)) return -1;
+
+  const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(k));
+  const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(k));
+  const float step_size = static_cast<float>(static_cast<double>(lr) / bc1);
+  const float sqrt_bc2 = static_cast<float>(std::sqrt(bc2));
+  const float omb1 = 1.0f - beta1;
+  const float omb2 = 1.0f - beta2;
+  const float decay = 1.0f - lr * weight_decay;
+
+  int32_t s = 0;
+  double acc = 0.0;
+  for (int64_t j = 0; j < n; ++j) {
+    union { uint32_t u; float f; } cv;
+    cv.u = static_cast<uint32_t>(grad_bf16[j]) << 16;
+    const float g = cv.f;
+    const float p0 = p_in[j];
+    const float m1 = beta1 * exp_avg[j] + omb1 * g;
+    const float v = beta2 * exp_avg_sq[j] + (omb2 * g) * g;
+    const float pd = p0 * decay;
+    const float denom = std::sqrt(v) / sqrt_bc2 + eps;
+    const float upd = step_size * (m1 / denom);
+    const float p1 = pd - upd;
+    exp_avg[j] = m1;
+    exp_avg_sq[j] = v;
+    p_out[j] = p1;
+    if (dout) dout[j] = anchor[j] - p1;
+    if (step_sq_out) {
+      while (s < S && j >= seg_off[s + 1]) { step_sq_out[s] = acc; acc = 0.0; ++s; }
+      const double df = static_cast<double>(p1 - p0);
+      acc += df * df;
+    }
+  }
+  if (step_sq_out) {
+    while (s < S) { step_sq_out[s] = acc; acc = 0.0; ++s; }
+  }
+  return 0;
+}
+
+int co2_oracle_adamw_f64(int64_t n, double* p, const double* grad,
+                         double* exp_avg, double* exp_avg_sq, double lr,
+                         double beta1, double beta2, double eps,
+                         double weight_decay, int64_t k) {
+  if (n < 0 || !p || !grad || !exp_avg || !exp_avg_sq || k < 1) return -1;
+  const double bc1 = 1.0 - std::pow(beta1, static_cast<double>(k));
+  const double bc2 = 1.0 - std::pow(beta2, static_cast<double>(k));
+  for (int64_t j = 0; j < n; ++j) {
+    const double g = grad[j];
+    const double m1 = beta1 * exp_avg[j] + (1.0 - beta1) * g;
+    const double v = beta2 * exp_avg_sq[j] + (1.0 - beta2) * g * g;
+    double pj = p[j] * (1.0 - lr * weight_decay);
+    pj -= (lr / bc1) * m1 / (std::sqrt(v) / std::sqrt(bc2) + eps);
+    exp_avg[j] = m1;
+    exp_avg_sq[j] = v;
+    p[j] = pj;
+  }
+  return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,414 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, none of
+which is the oracle's own formula retyped.
+
+  P0  hand-expanded four-coordinate example (tests/golden), all readings of Eq. 3
+  P1  K=1, c=0, no clipping  == library momentum SGD on the pseudo-gradient
+      (the SlowMo form the paper starts from in Section 3.2); beta=0, alpha=1
+      == plain parameter averaging (Section 3.1, Local-SGD)
+  P2  K identical workers == one worker
+  P3  mean_k(a - x_k) == a - mean_k x_k  (appendix, local update rule summed)
+  P4  |Clip| <= phi, |x' - a| <= alpha*phi, clipped count
+  P5  Lambda >= 1, == 1 for c=0 or m=0, affine in c and alpha, inverse in T
+  P6  alpha*sqrt(M2) at round t == ||anchor_t - anchor_{t-1}|| from saved anchors
+  P7  geometric closed form of the momentum; heavy-ball recursion (appendix)
+  P8  first round == general update with m=0 and zero deltas
+  P10 AdamW == library AdamW; lr=0 leaves params alone
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "outer_step_worked_example.json")
+INF = float("inf")
+
+
+def f32(a):
+    """Fresh contiguous fp32 copy (never a view of the argument)."""
+    return np.array(a, dtype=np.float32, copy=True, order="C")
+
+
+def f64(a):
+    """Fresh contiguous fp64 copy (never a view of the argument)."""
+    return np.array(a, dtype=np.float64, copy=True, order="C")
+
+
+def rng_state(seed, n, K, m_std=0.02, drift=1e-3):
+    r = np.random.default_rng(seed)
+    a = f32(r.normal(0, 0.02, n))
+    x = f32(a + r.normal(0, drift, n))
+    m = f32(r.normal(0, m_std, n))
+    d = [f32(r.normal(0, drift, n)) for _ in range(K)]
+    return a, x, m, d
+
+
+# ---------------------------------------------------------------- P0
+with open(GOLDEN) as fh:
+    _G = json.load(fh)
+
+
+@pytest.mark.parametrize("case", _G["cases"], ids=[c["name"] for c in _G["cases"]])
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_p0_hand_expanded_example(oracle, case, prec):
+    c = _G["common"]
+    conv = f32 if prec == "f32" else f64
+    tol = 2e-7 if prec == "f32" else 2e-9   # fixture is rounded at the 9th digit
+    a, x, m = conv(c["a"]), conv(c["x"]), conv(c["m"])
+    d = [conv(c["d0"]), conv(c["d1"])]
+    fs = None if case["first_step_norm"] is None else conv(case["first_step_norm"])
+    fn = oracle.outer_step_f32 if prec == "f32" else oracle.outer_step_f64
+    out = fn(seg_off=case["seg_off"], alpha=c["alpha"], beta=c["beta"], phi=c["phi"],
+             c=c["c"], tau=c["tau"], step=c["step"], x=x, a=a, m=m, deltas=d,
+             first_step_norm=fs)
+    # a - x cancels: accurate to the rounding of its operands (|a|, |x| <= 2.1)
+    np.testing.assert_allclose(out["dout"], c["dout"], rtol=0, atol=2.1 * tol)
+    np.testing.assert_allclose(out["lam"], case["lambda"], rtol=tol)
+    np.testing.assert_allclose(m, case["m_new"], rtol=tol)
+    np.testing.assert_allclose(x, case["x_new"], rtol=tol)
+    np.testing.assert_allclose(a, case["x_new"], rtol=tol)   # anchor <- x_{t+1,0}
+    if prec == "f32":
+        assert out["nclipped"] == case["nclipped"]
+
+
+def test_p0_separate_anchor_out_and_split_form(oracle):
+    """anchor_out != anchor leaves the anchor alone; x=None skips dout/params."""
+    c, case = _G["common"], _G["cases"][0]
+    a, m = f32(c["a"]), f32(c["m"])
+    a_out = np.zeros(4, np.float32)
+    out = oracle.outer_step_f32(seg_off=case["seg_off"], alpha=c["alpha"], beta=c["beta"],
+                                phi=c["phi"], c=c["c"], tau=c["tau"], step=1, x=None, a=a,
+                                a_out=a_out, m=m, deltas=[f32(c["d0"]), f32(c["d1"])],
+                                first_step_norm=f32(case["first_step_norm"]))
+    assert out["dout"] is None
+    np.testing.assert_array_equal(a, f32(c["a"]))
+    np.testing.assert_allclose(a_out, case["x_new"], rtol=2e-7)
+    np.testing.assert_allclose(m, case["m_new"], rtol=2e-7)
+
+
+# ---------------------------------------------------------------- P1
+def test_p1_reduces_to_library_momentum_sgd(oracle):
+    n, alpha, beta, T = 257, 0.7, 0.9, 5
+    r = np.random.default_rng(1)
+    a0 = r.normal(0, 0.02, n)
+    grads = [r.normal(0, 1e-3, n) for _ in range(T)]
+
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=alpha, momentum=beta, dampening=0.0, nesterov=False)
+
+    a, m = f64(a0), np.zeros(n)
+    for t in range(T):
+        p.grad = torch.tensor(grads[t], dtype=torch.float64)
+        opt.step()
+        x = f64(a - 0.5 * grads[t])            # any local params: only dout depends on them
+        oracle.outer_step_f64(seg_off=[0, 100, n], alpha=alpha, beta=beta, phi=INF, c=0.0,
+                              tau=3, step=t + 1, x=x, a=a, m=m, deltas=[f64(grads[t])])
+        np.testing.assert_allclose(a, p.detach().numpy(), rtol=1e-13, atol=1e-16)
+        np.testing.assert_array_equal(x, a)
+
+    # fp32 evaluation follows the same trajectory to fp32 accuracy
+    a32, m32 = f32(a0), np.zeros(n, np.float32)
+    for t in range(T):
+        oracle.outer_step_f32(seg_off=[0, 100, n], alpha=alpha, beta=beta, phi=INF, c=0.0,
+                              tau=3, step=t + 1, x=f32(a32), a=a32, m=m32,
+                              deltas=[f32(grads[t])])
+    np.testing.assert_allclose(a32, a, rtol=0, atol=2e-7 * T)
+
+
+def test_p1_plain_parameter_averaging(oracle):
+    n, K = 131, 5
+    r = np.random.default_rng(2)
+    a0 = r.normal(0, 0.02, n)
+    xs = [a0 + r.normal(0, 1e-3, n) for _ in range(K)]
+    a, m = f64(a0), f64(r.normal(0, 1, n))       # beta = 0 must erase old momentum
+    oracle.outer_step_f64(seg_off=[0, n], alpha=1.0, beta=0.0, phi=INF, c=0.0, tau=1, step=1,
+                          x=f64(xs[0]), a=a, m=m, deltas=[f64(a0 - xk) for xk in xs])
+    np.testing.assert_allclose(a, np.mean(xs, axis=0), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- P2
+@pytest.mark.parametrize("K", [2, 4, 8, 16])
+def test_p2_identical_workers_equal_single_worker(oracle, K):
+    n = 1000
+    a, x, m, d = rng_state(3, n, 1)
+    kw = dict(seg_off=[0, 10, 500, n], alpha=1.0, beta=0.9, phi=0.01, c=1.0, tau=4, step=2)
+    a1, x1, m1 = a.copy(), x.copy(), m.copy()
+    o1 = oracle.outer_step_f32(x=x1, a=a1, m=m1, deltas=[d[0]], **kw)
+    aK, xK, mK = a.copy(), x.copy(), m.copy()
+    oK = oracle.outer_step_f32(x=xK, a=aK, m=mK, deltas=[d[0]] * K, **kw)
+    np.testing.assert_array_equal(o1["lam"], oK["lam"])
+    if K == 2:
+        # d + d and the product with 1/2 are exact, so bits agree
+        np.testing.assert_array_equal(m1, mK)
+        np.testing.assert_array_equal(a1, aK)
+    else:
+        # the left-to-right sum d+d+...+d rounds at 3d, 5d, ...: each of the
+        # K-1 additions is off by at most half an ulp of the running sum; the
+        # final sum beta*m + dbar/Lambda may then round one ulp of m' apart
+        bound = K * 2.0 ** -24 * np.abs(d[0].astype(np.float64)) + 1e-45
+        assert np.all(np.abs(m1.astype(np.float64) - mK)
+                      <= bound + 2.0 ** -23 * np.abs(m1.astype(np.float64)))
+        assert np.all(np.abs(a1.astype(np.float64) - aK)
+                      <= bound + 2.0 ** -23 * np.abs(m1.astype(np.float64))
+                      + 2.0 ** -23 * np.abs(a1.astype(np.float64)))
+
+
+def test_p2_identical_workers_non_power_of_two(oracle):
+    n = 1000
+    a, x, m, d = rng_state(4, n, 1)
+    kw = dict(seg_off=[0, n], alpha=1.0, beta=0.9, phi=INF, c=1.0, tau=4, step=2)
+    a1, m1 = f64(a), f64(m)
+    oracle.outer_step_f64(x=f64(x), a=a1, m=m1, deltas=[f64(d[0])], **kw)
+    a3, m3 = f64(a), f64(m)
+    oracle.outer_step_f64(x=f64(x), a=a3, m=m3, deltas=[f64(d[0])] * 3, **kw)
+    np.testing.assert_allclose(m3, m1, rtol=1e-14, atol=1e-18)
+    np.testing.assert_allclose(a3, a1, rtol=1e-14)
+
+
+# ---------------------------------------------------------------- P3
+def test_p3_mean_of_deltas_is_delta_of_mean(oracle):
+    n, K = 300, 8
+    r = np.random.default_rng(5)
+    a0 = r.normal(0, 0.02, n)
+    xs = [a0 + r.normal(0, 1e-3, n) for _ in range(K)]
+    m0 = r.normal(0, 0.01, n)
+    kw = dict(seg_off=[0, 7, n], alpha=0.9, beta=0.8, phi=INF, c=1.0, tau=2, step=1,
+              first_step_norm=f64([0.01, 0.02]))
+    a1, m1 = f64(a0), f64(m0)
+    oracle.outer_step_f64(x=f64(xs[0]), a=a1, m=m1, deltas=[f64(a0 - xk) for xk in xs], **kw)
+    a2, m2 = f64(a0), f64(m0)
+    oracle.outer_step_f64(x=f64(xs[0]), a=a2, m=m2,
+                          deltas=[f64(a0 - np.mean(xs, axis=0))], **kw)
+    np.testing.assert_allclose(m1, m2, rtol=1e-11, atol=1e-16)
+    np.testing.assert_allclose(a1, a2, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- P4
+@pytest.mark.parametrize("phi", [1e-3, 5e-3, 1.0])
+def test_p4_clipping_bounds_and_count(oracle, phi):
+    n, alpha = 5000, 0.75
+    a, x, m, d = rng_state(6, n, 4, m_std=0.02)
+    a_old, m_old = a.copy(), m.copy()
+    out = oracle.outer_step_f32(seg_off=[0, 1234, n], alpha=alpha, beta=0.9, phi=phi, c=0.5,
+                                tau=4, step=1, x=x, a=a, m=m, deltas=d)
+    moved = np.abs(a.astype(np.float64) - a_old.astype(np.float64))
+    assert moved.max() <= alpha * phi * (1 + 2.0 ** -22) + np.abs(a_old).max() * 2.0 ** -23
+    assert out["nclipped"] == int(np.count_nonzero(np.abs(m) > np.float32(phi)))
+    if phi < 0.01:
+        assert out["nclipped"] > n // 2       # the clamp branch is really exercised
+        clipped = np.abs(m) > np.float32(phi)
+        # clipped coordinates move by exactly alpha*phi (up to rounding of x)
+        np.testing.assert_allclose(moved[clipped], alpha * phi, rtol=1e-4)
+        # and in the direction opposite to the momentum's sign
+        assert np.all(np.sign(a_old[clipped] - a[clipped]) == np.sign(m[clipped]))
+    np.testing.assert_array_equal(x, a)
+    assert not np.array_equal(m, m_old)
+
+
+# ---------------------------------------------------------------- P5
+def test_p5_lambda_properties(oracle):
+    n = 4096
+    a, x, m, d = rng_state(7, n, 2)
+    seg = [0, 100, 100, 3000, n]              # includes an empty segment
+    base = dict(seg_off=seg, beta=0.9, phi=1.0, tau=4, step=1)
+
+    def lam(c=1.0, alpha=1.0, mm=m, fs=None, tau=4):
+        kw = dict(base); kw["tau"] = tau
+        o = oracle.outer_step_f32(alpha=alpha, c=c, x=x.copy(), a=a.copy(), m=mm.copy(),
+                                  deltas=d, first_step_norm=fs, **kw)
+        return o["lam"].astype(np.float64)
+
+    L1 = lam()
+    assert np.all(L1 >= 1.0) and L1[1] == 1.0          # empty segment: T = 0 -> 1
+    assert np.all(L1[[0, 2, 3]] > 1.0)
+    assert np.all(lam(c=0.0) == 1.0)
+    assert np.all(lam(mm=np.zeros_like(m)) == 1.0)
+    np.testing.assert_allclose(lam(c=2.0) - 1, 2 * (L1 - 1), rtol=1e-6)
+    np.testing.assert_allclose(lam(alpha=0.5) - 1, 0.5 * (L1 - 1), rtol=1e-6)
+    fs = f32([0.01, 0.01, 0.02, 0.04])
+    Lf = lam(fs=fs)
+    np.testing.assert_allclose(lam(fs=f32(2 * fs)) - 1, (Lf - 1) / 2, rtol=1e-6)
+    np.testing.assert_allclose(lam(fs=fs, tau=8) - 1, (Lf - 1) / 2, rtol=1e-6)
+    # against the definition: numerator is the norm of the clipped old momentum
+    num = np.sqrt(np.add.reduceat(np.clip(m.astype(np.float64), -1, 1) ** 2, [0, 100, 3000]))
+    np.testing.assert_allclose(Lf[[0, 2, 3]], num / (4 * fs[[0, 2, 3]].astype(np.float64)) + 1,
+                               rtol=1e-6)
+
+
+# ---------------------------------------------------------------- P6
+def test_p6_numerator_equals_anchor_displacement(oracle):
+    n, K, alpha, phi = 6000, 3, 0.8, 2e-3
+    seg = [0, 1000, 2500, n]
+    r = np.random.default_rng(8)
+    a = f64(r.normal(0, 0.02, n))
+    m = np.zeros(n)
+    anchors = [a.copy()]
+    for t in range(1, 6):
+        d = [f64(r.normal(0, 1e-3, n)) for _ in range(K)]
+        prev_m = m.copy()
+        out = oracle.outer_step_f32(seg_off=seg, alpha=alpha, beta=0.9, phi=phi, c=1.0, tau=2,
+                                    step=t, x=f32(a), a=(a32 := f32(a)), m=(m32 := f32(m)),
+                                    deltas=[f32(v) for v in d])
+        # redo in fp64 to carry an accurate trajectory
+        oracle.outer_step_f64(seg_off=seg, alpha=alpha, beta=0.9, phi=phi, c=1.0, tau=2,
+                              step=t, x=f64(a), a=a, m=m, deltas=d)
+        anchors.append(a.copy())
+        if t >= 2:
+            disp = anchors[t - 1] - anchors[t - 2]      # x_{t,0} - x_{t-1,0} seen at round t
+            want = np.sqrt(np.add.reduceat(disp ** 2, seg[:-1]))
+            got = alpha * np.sqrt(out["M2"])
+            np.testing.assert_allclose(got, want, rtol=1e-5)
+            assert np.any(np.abs(prev_m) > phi)          # clipping took part in the identity
+
+
+# ---------------------------------------------------------------- P7
+def test_p7_geometric_momentum_and_heavy_ball(oracle):
+    n, alpha, beta, T = 64, 0.3, 0.85, 12
+    r = np.random.default_rng(9)
+    g = r.normal(0, 1e-3, n)
+    a, m = f64(r.normal(0, 0.02, n)), np.zeros(n)
+    hist = [a.copy()]
+    for t in range(1, T + 1):
+        oracle.outer_step_f64(seg_off=[0, n], alpha=alpha, beta=beta, phi=INF, c=0.0, tau=1,
+                              step=t, x=f64(a), a=a, m=m, deltas=[f64(g)])
+        hist.append(a.copy())
+        np.testing.assert_allclose(m, g * (1 - beta ** t) / (1 - beta), rtol=1e-12)
+    for t in range(1, T):
+        lhs = hist[t + 1] - hist[t]
+        rhs = beta * (hist[t] - hist[t - 1]) - alpha * g
+        np.testing.assert_allclose(lhs, rhs, rtol=1e-9, atol=1e-18)
+
+
+def test_p7_heavy_ball_with_penalty(oracle):
+    """x_{t+1}-x_t = beta (x_t-x_{t-1}) - (alpha/Lambda_t) dbar_t while nothing clips."""
+    n, alpha, beta = 500, 0.6, 0.7
+    seg = [0, 200, n]
+    r = np.random.default_rng(10)
+    a, m = f64(r.normal(0, 0.02, n)), np.zeros(n)
+    hist = [a.copy()]
+    for t in range(1, 7):
+        d = [f64(r.normal(0, 1e-3, n)) for _ in range(2)]
+        out = oracle.outer_step_f64(seg_off=seg, alpha=alpha, beta=beta, phi=INF, c=1.0,
+                                    tau=3, step=t, x=f64(a), a=a, m=m, deltas=d)
+        hist.append(a.copy())
+        if t >= 2:
+            lam = np.repeat(out["lam"], np.diff(seg))
+            assert np.all(out["lam"] > 1.0)
+            lhs = hist[t] - hist[t - 1]
+            rhs = beta * (hist[t - 1] - hist[t - 2]) - alpha / lam * (d[0] + d[1]) / 2
+            np.testing.assert_allclose(lhs, rhs, rtol=1e-8, atol=1e-17)
+
+
+# ---------------------------------------------------------------- P8
+def test_p8_first_round(oracle):
+    n = 777
+    a, x, m, d = rng_state(11, n, 2)
+    m[:] = 0
+    a0, x0 = a.copy(), x.copy()
+    out = oracle.outer_step_f32(seg_off=[0, 5, n], alpha=1.0, beta=0.9, phi=1.0, c=1.0, tau=4,
+                                step=0, x=x, a=a, m=m, deltas=None)
+    np.testing.assert_array_equal(out["dout"], a0 - x0)
+    np.testing.assert_array_equal(x, a0)
+    np.testing.assert_array_equal(a, a0)
+    assert not m.any() and np.all(out["lam"] == 1.0)
+    # the general update with m = 0 and zero deltas lands on the same state
+    a2, x2, m2 = a0.copy(), x0.copy(), np.zeros(n, np.float32)
+    z = [np.zeros(n, np.float32)] * 2
+    out2 = oracle.outer_step_f32(seg_off=[0, 5, n], alpha=1.0, beta=0.9, phi=1.0, c=1.0,
+                                 tau=4, step=1, x=x2, a=a2, m=m2, deltas=z)
+    np.testing.assert_array_equal(out2["dout"], out["dout"])
+    np.testing.assert_array_equal(x2, a0)
+    np.testing.assert_array_equal(a2, a0)
+    assert not m2.any()
+
+
+# ---------------------------------------------------------------- norms
+def test_sqnorms_against_numpy(oracle):
+    r = np.random.default_rng(12)
+    buf = f32(r.normal(0, 1, 10007))
+    seg = [0, 1, 1, 4096, 9000, 10007]
+    got = oracle.sqnorms(buf, seg)
+    b64 = buf.astype(np.float64)
+    want = [float(np.dot(b64[lo:hi], b64[lo:hi])) for lo, hi in zip(seg, seg[1:])]
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+    gotc = oracle.sqnorms(buf, seg, phi=0.5)
+    c64 = np.clip(b64, -0.5, 0.5)
+    wantc = [float(np.dot(c64[lo:hi], c64[lo:hi])) for lo, hi in zip(seg, seg[1:])]
+    np.testing.assert_allclose(gotc, wantc, rtol=1e-13)
+
+
+def test_f32_evaluation_tracks_f64_truth(oracle):
+    """The fp32-ordered oracle stays within fp32 rounding of the fp64 one,
+    measured against the magnitude of the operands of each sum."""
+    n, K = 20000, 8
+    a, x, m, d = rng_state(13, n, K)
+    seg = [0, 3, 4000, 4001, n]
+    kw = dict(seg_off=seg, alpha=1.0, beta=0.95, phi=0.02, c=1.0, tau=4, step=1)
+    a32, x32, m32 = a.copy(), x.copy(), m.copy()
+    o32 = oracle.outer_step_f32(x=x32, a=a32, m=m32, deltas=d, **kw)
+    a64, x64, m64 = f64(a), f64(x), f64(m)
+    o64 = oracle.outer_step_f64(x=x64, a=a64, m=m64, deltas=[f64(v) for v in d], **kw)
+    np.testing.assert_allclose(o32["lam"], o64["lam"], rtol=2e-7)
+    lam = np.repeat(o64["lam"], np.diff(seg))
+    dbar = np.mean([f64(v) for v in d], axis=0)
+    scale_m = np.abs(0.95 * f64(m)) + np.abs(dbar / lam)
+    assert np.all(np.abs(m32 - m64) <= 1e-6 * scale_m)
+    scale_x = np.abs(f64(a)) + np.abs(np.clip(m64, -0.02, 0.02))
+    assert np.all(np.abs(a32 - a64) <= 1e-6 * scale_x)
+    assert np.all(np.abs(o32["dout"] - o64["dout"]) <= 1e-7 * (np.abs(f64(a)) + np.abs(f64(x))))
+
+
+# ---------------------------------------------------------------- P10
+def _bf16_bits(v):
+    t = torch.tensor(v, dtype=torch.float32).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().astype(np.uint16), t.to(torch.float64).numpy()
+
+
+def test_p10_adamw_against_library(oracle):
+    n, steps = 513, 6
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    r = np.random.default_rng(14)
+    p0 = r.normal(0, 0.02, n)
+    p_t = torch.nn.Parameter(torch.tensor(p0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p_t], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]),
+                            eps=hp["eps"], weight_decay=hp["weight_decay"], amsgrad=False)
+    p64, m64, v64 = f64(p0), np.zeros(n), np.zeros(n)
+    p32, m32, v32 = f32(p0), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for k in range(1, steps + 1):
+        bits, g = _bf16_bits(r.normal(0, 1e-3, n))
+        p_t.grad = torch.tensor(g)
+        opt.step()
+        oracle.adamw_f64(p=p64, grad=f64(g), exp_avg=m64, exp_avg_sq=v64, k=k, **hp)
+        np.testing.assert_allclose(p64, p_t.detach().numpy(), rtol=1e-12, atol=1e-15)
+        oracle.adamw_f32(p_in=p32, p_out=p32, grad_bf16=bits, exp_avg=m32, exp_avg_sq=v32,
+                         k=k, **hp)
+        np.testing.assert_allclose(p32, p64, rtol=0, atol=3e-7 * k * (np.abs(p0).max() + 1e-3))
+        # exp_avg is a cancelling sum of terms of size ~1e-3: absolute bound
+        np.testing.assert_allclose(m32, m64, rtol=0, atol=1e-3 * 1e-6)
+        np.testing.assert_allclose(v32, v64, rtol=1e-5, atol=1e-16)
+
+
+def test_p10_adamw_epilogues_and_lr_zero(oracle):
+    n = 1000
+    seg = [0, 10, 10, 600, n]
+    r = np.random.default_rng(15)
+    p0, anchor = f32(r.normal(0, 0.02, n)), f32(r.normal(0, 0.02, n))
+    bits, g = _bf16_bits(r.normal(0, 1e-3, n))
+    hp = dict(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    p1 = np.empty_like(p0)
+    out = oracle.adamw_f32(p_in=p0, p_out=p1, grad_bf16=bits, exp_avg=np.zeros(n, np.float32),
+                           exp_avg_sq=np.zeros(n, np.float32), lr=3e-4, k=1, anchor=anchor,
+                           seg_off=seg, want_step_sq=True, **hp)
+    np.testing.assert_array_equal(out["dout"], anchor - p1)
+    df = (p1 - p0).astype(np.float64)
+    want = [float(np.dot(df[lo:hi], df[lo:hi])) for lo, hi in zip(seg, seg[1:])]
+    np.testing.assert_allclose(out["step_sq"], want, rtol=1e-13)
+    # closed form of the first step from zero state: bias correction cancels the
+    # (1-beta) factors, leaving p*(1-lr*wd) - lr*g/(|g|+eps)
+    closed = p0.astype(np.float64) * (1 - 3e-4 * 0.1) - 3e-4 * g / (np.abs(g) + 1e-8)
+    np.testing.assert_allclose(p1, closed, rtol=0, atol=2e-7 * 0.1)
+    p2 = np.empty_like(p0)
+    oracle.adamw_f32(p_in=p0, p_out=p2, grad_bf16=bits, exp_avg=np.zeros(n, np.float32),
+                     exp_avg_sq=np.zeros(n, np.float32), lr=0.0, k=1, **hp)
+    np.testing.assert_array_equal(p2, p0)

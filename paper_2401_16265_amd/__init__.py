@@ -1,0 +1,13 @@
+"""MI355X-native CO2 outer update: thin Python binding over libco2.so.
+
+The package marshals arguments only; every step of the update runs in the HIP
+kernels behind the C ABI declared in include/co2.h.  There is no CPU fallback:
+if the library cannot be built or loaded, importing the binding's functions
+raises.
+"""
+from .binding import (  # noqa: F401
+    CO2_OK, CO2_EINVAL, CO2_EWORKSPACE, CO2_EHIP, CO2_MAX_K, CO2_MAX_NORM_BUFS,
+    CO2_FLAG_NONE, CO2_FLAG_CARRIED_NORMS,
+    Co2Error, Co2Params, SegmentTable, HipEvent, make_params, lib, lib_path, strerror, workspace_bytes,
+    co2_outer_step, co2_pseudo_grad_norms, co2_inner_adamw, co2_sqrt_to_f32, co2_copy_f32,
+)

@@ -1,0 +1,141 @@
+// Fused AdamW local update (CO2 paper, Algorithm 1, "LU" line with AdamW as the
+// base optimizer; decoupled weight decay as in Loshchilov & Hutter), fp32 master
+// weights and moments, bf16 gradients.  14 bytes read and 12 written per
+// coordinate; optionally also forms the round's pseudo-gradient anchor - p'
+// (the payload of the all-reduce launched after the last inner step) and the
+// per-segment sum of squares of the step p' - p_in (the first inner step's norm
+// is the denominator of the staleness gap, Eq. 3).
+#include "co2_device.hpp"
+#include "co2_launch.hpp"
+
+namespace co2 {
+
+struct AdamScalars {
+  float beta1, beta2, omb1, omb2, decay, step_size, sqrt_bc2, eps;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+
+// One coordinate; every fp32 operation rounded once, IEEE sqrt and division.
+__device__ __forceinline__ float adamw_coord(float p, float g, float& m1, float& v,
+                                             const AdamScalars& h) {
+  const float t1 = h.beta1 * m1;
+  const float t2 = h.omb1 * g;
+  m1 = t1 + t2;
+  const float t3 = h.beta2 * v;
+  const float t4 = (h.omb2 * g) * g;
+  v = t3 + t4;
+  const float pd = p * h.decay;
+  const float denom = __fdiv_rn(__fsqrt_rn(v), h.sqrt_bc2) + h.eps;
+  const float upd = h.step_size * __fdiv_rn(m1, denom);
+  return pd - upd;
+}
+
+template <bool HAS_DOUT, bool HAS_NORM>
+__global__ __launch_bounds__(kBlock) void adamw_step(
+    int64_t n, const float* p_in, float* p_out, const uint16_t* __restrict__ grad,
+    float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq, AdamScalars h,
+    const float* __restrict__ anchor, float* __restrict__ dout,
+    const int64_t* __restrict__ off, int S, double* __restrict__ part) {
+  __shared__ double lds[kWavesPerBlock];
+  constexpr int U = 2;
+  constexpr int64_t kTile = kAdamTile;
+  const int64_t tile = blockIdx.x;
+  const int64_t base = tile * kTile;
+  int s_lo = 0;
+  bool one_segment = true;
+  if (HAS_NORM) {
+    s_lo = seg_of(off, S, base);
+    one_segment = base + kTile <= off[s_lo + 1];
+  }
+
+  if (base + kTile <= n && one_segment) {
+    float4 vp[U], vm[U], vv[U], va[U];
+    uint2 vg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t j = base + ((int64_t(u) * kBlock + threadIdx.x) << 2);
+      vp[u] = ld4(p_in + j);
+      vg[u] = *reinterpret_cast<const uint2*>(grad + j);
+      vm[u] = ld4(exp_avg + j);
+      vv[u] = ld4(exp_avg_sq + j);
+      if (HAS_DOUT) va[u] = ld4(anchor + j);
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t j = base + ((int64_t(u) * kBlock + threadIdx.x) << 2);
+      const float pc[4] = {vp[u].x, vp[u].y, vp[u].z, vp[u].w};
+      float mc[4] = {vm[u].x, vm[u].y, vm[u].z, vm[u].w};
+      float vc[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+      const float gc[4] = {bf16_to_f32(vg[u].x & 0xFFFFu), bf16_to_f32(vg[u].x >> 16),
+                           bf16_to_f32(vg[u].y & 0xFFFFu), bf16_to_f32(vg[u].y >> 16)};
+      float po[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        po[e] = adamw_coord(pc[e], gc[e], mc[e], vc[e], h);
+        if (HAS_NORM) acc += sq(po[e] - pc[e]);
+      }
+      st4(exp_avg + j, make_float4(mc[0], mc[1], mc[2], mc[3]));
+      st4(exp_avg_sq + j, make_float4(vc[0], vc[1], vc[2], vc[3]));
+      st4(p_out + j, make_float4(po[0], po[1], po[2], po[3]));
+      if (HAS_DOUT) {
+        const float ac[4] = {va[u].x, va[u].y, va[u].z, va[u].w};
+        st4(dout + j, make_float4(ac[0] - po[0], ac[1] - po[1], ac[2] - po[2], ac[3] - po[3]));
+      }
+    }
+    if (HAS_NORM) {
+      const double t = block_sum(acc, lds);
+      if (threadIdx.x == 0) part[tile + s_lo] = t;
+    }
+    return;
+  }
+
+  // Boundary or ragged tile: one wavefront per segment piece.
+  const int64_t end = (base + kTile < n) ? base + kTile : n;
+  const int s_hi = HAS_NORM ? seg_of(off, S, end - 1) : 0;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  for (int s = s_lo + wave; s <= s_hi; s += kWavesPerBlock) {
+    int64_t lo = base, hi = end;
+    if (HAS_NORM) {
+      lo = off[s] > base ? off[s] : base;
+      hi = off[s + 1] < end ? off[s + 1] : end;
+    }
+    if (lo >= hi) continue;
+    double acc = 0.0;
+    for (int64_t j = lo + lane; j < hi; j += kWave) {
+      const float p = p_in[j];
+      float m1 = exp_avg[j], v = exp_avg_sq[j];
+      const float pn = adamw_coord(p, bf16_to_f32(grad[j]), m1, v, h);
+      exp_avg[j] = m1;
+      exp_avg_sq[j] = v;
+      p_out[j] = pn;
+      if (HAS_DOUT) dout[j] = anchor[j] - pn;
+      if (HAS_NORM) acc += sq(pn - p);
+    }
+    if (HAS_NORM) {
+      const double t = wave_sum(acc);
+      if (lane == 0) part[tile + s] = t;
+    }
+  }
+}
+
+hipError_t launch_adamw(const AdamArgs& g, hipStream_t st) {
+  const unsigned tiles = static_cast<unsigned>((g.n + kAdamTile - 1) / kAdamTile);
+  const AdamScalars h{g.beta1, g.beta2, g.omb1, g.omb2, g.decay, g.step_size, g.sqrt_bc2, g.eps};
+  const bool has_dout = g.dout != nullptr, has_norm = g.part != nullptr;
+#define CO2_ADAM_LAUNCH(D, N)                                                              \
+  hipLaunchKernelGGL((adamw_step<D, N>), dim3(tiles), dim3(kBlock), 0, st, g.n, g.p_in,    \
+                     g.p_out, g.grad, g.exp_avg, g.exp_avg_sq, h, g.anchor, g.dout,        \
+                     g.off_dev, g.S, g.part)
+  if (has_dout && has_norm) CO2_ADAM_LAUNCH(true, true);
+  else if (has_dout) CO2_ADAM_LAUNCH(true, false);
+  else if (has_norm) CO2_ADAM_LAUNCH(false, true);
+  else CO2_ADAM_LAUNCH(false, false);
+#undef CO2_ADAM_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace co2

@@ -1,0 +1,318 @@
+// C ABI of libco2 (see include/co2.h): host-side validation, workspace layout,
+// kernel sequencing.  Nothing here allocates, synchronises or keeps device
+// state; every call enqueues on the caller's stream and returns.
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "co2.h"
+#include "co2_launch.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int fail_hip(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return CO2_EHIP;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+inline size_t round256(size_t b) { return (b + 255u) & ~size_t(255u); }
+
+// [p, p+bytes) ranges overlap?
+inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+  if (!a || !b) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+inline bool table_ok(int64_t n, int32_t S, const int64_t* seg_off) {
+  if (n < 1 || S < 1 || !seg_off) return false;
+  if (seg_off[0] != 0 || seg_off[S] != n) return false;
+  for (int32_t s = 0; s < S; ++s)
+    if (seg_off[s + 1] < seg_off[s]) return false;
+  return true;
+}
+
+// Workspace regions (all 256-byte aligned).  Slot arrays hold one fp64 partial
+// per (tile, segment) pair, indexed tile + segment.
+struct Workspace {
+  double* norm_part[2];    // pass-1 partials (kNormTile tiles): clipped momentum, deltas[0]
+  double* carry_part[2];   // partials left by the sweep (kSweepTile tiles) for the next round
+  double* adam_part;       // partials of the AdamW step norm (kAdamTile tiles)
+  double* seg_sq;          // [2][S] per-segment sums
+  float* inv;              // [S] 1/Lambda
+  size_t bytes;
+};
+
+inline int64_t slots_of(int64_t n, int64_t tile, int32_t S) { return (n + tile - 1) / tile + S; }
+
+inline Workspace layout(void* base, int64_t n, int32_t S) {
+  Workspace w{};
+  char* p = static_cast<char*>(base);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    char* r = p ? p + o : nullptr;
+    o += round256(bytes);
+    return r;
+  };
+  const size_t sn = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kNormTile, S));
+  const size_t ss = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kSweepTile, S));
+  const size_t sa = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kAdamTile, S));
+  w.norm_part[0] = reinterpret_cast<double*>(take(sn));
+  w.norm_part[1] = reinterpret_cast<double*>(take(sn));
+  w.carry_part[0] = reinterpret_cast<double*>(take(ss));
+  w.carry_part[1] = reinterpret_cast<double*>(take(ss));
+  w.adam_part = reinterpret_cast<double*>(take(sa));
+  w.seg_sq = reinterpret_cast<double*>(take(sizeof(double) * 2 * static_cast<size_t>(S)));
+  w.inv = reinterpret_cast<float*>(take(sizeof(float) * static_cast<size_t>(S)));
+  w.bytes = o;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t co2_workspace_bytes(int64_t n, int32_t S, int32_t K) {
+  if (n < 1 || S < 1 || K < 1 || K > CO2_MAX_K) return 0;
+  return layout(nullptr, n, S).bytes;
+}
+
+const char* co2_strerror(int code) {
+  switch (code) {
+    case CO2_OK: return "ok";
+    case CO2_EINVAL: return "invalid argument (NULL, out of range, misaligned or overlapping buffer)";
+    case CO2_EWORKSPACE: return "workspace missing, misaligned or smaller than co2_workspace_bytes()";
+    case CO2_EHIP: return "HIP kernel launch failed (see co2_last_hip_error())";
+    default: return "unknown co2 error code";
+  }
+}
+
+int co2_last_hip_error(void) { return g_last_hip_error; }
+
+int co2_outer_step(const co2_params* p, float* params, const float* anchor, float* anchor_out,
+                   float* momentum, const float* const* deltas, float* delta_out,
+                   const float* first_step_norm, float* lambda_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  // ---- validation (no side effects before it passes)
+  if (!p) return CO2_EINVAL;
+  if (!table_ok(p->n, p->S, p->seg_off) || !p->seg_off_dev) return CO2_EINVAL;
+  if (p->K < 1 || p->K > CO2_MAX_K || p->tau < 1 || p->step < 0) return CO2_EINVAL;
+  if (!std::isfinite(p->alpha)) return CO2_EINVAL;
+  if (!(p->beta >= 0.0f && p->beta < 1.0f)) return CO2_EINVAL;
+  if (!(p->clip_phi > 0.0f)) return CO2_EINVAL;                 // also rejects NaN
+  if (!(p->penalty_c >= 0.0f) || !std::isfinite(p->penalty_c)) return CO2_EINVAL;
+  if (p->flags & ~CO2_FLAG_CARRIED_NORMS) return CO2_EINVAL;
+  if (!anchor || !anchor_out || !momentum) return CO2_EINVAL;
+  if ((params == nullptr) != (delta_out == nullptr)) return CO2_EINVAL;
+  const bool first = p->step == 0;
+  const bool carried = (p->flags & CO2_FLAG_CARRIED_NORMS) != 0;
+  if (first && carried) return CO2_EINVAL;
+  // Carried sums of delta_out^2 exist only if the previous call formed delta_out.
+  if (carried && !first_step_norm && !params) return CO2_EINVAL;
+  const size_t nb = sizeof(float) * static_cast<size_t>(p->n);
+  const size_t sb = sizeof(float) * static_cast<size_t>(p->S);
+  const void* vec[5] = {params, anchor, momentum, delta_out, anchor_out == anchor ? nullptr : anchor_out};
+  for (int i = 0; i < 5; ++i) {
+    if (!aligned16(vec[i])) return CO2_EINVAL;
+    for (int j = i + 1; j < 5; ++j)
+      if (overlaps(vec[i], nb, vec[j], nb)) return CO2_EINVAL;
+  }
+  if (!aligned16(p->seg_off_dev) || !aligned16(first_step_norm) || !aligned16(lambda_out))
+    return CO2_EINVAL;
+  if (overlaps(first_step_norm, sb, lambda_out, sb)) return CO2_EINVAL;
+  co2::DeltaPtrs dptr{};
+  if (!first) {
+    if (!deltas) return CO2_EINVAL;
+    for (int k = 0; k < p->K; ++k) {
+      const float* dk = deltas[k];
+      if (!dk || !aligned16(dk)) return CO2_EINVAL;
+      // inputs may repeat among themselves, but no output may touch them
+      if (overlaps(dk, nb, params, nb) || overlaps(dk, nb, momentum, nb) ||
+          overlaps(dk, nb, delta_out, nb) || overlaps(dk, nb, anchor_out, nb))
+        return CO2_EINVAL;
+      dptr.p[k] = dk;
+    }
+  }
+  const Workspace w = layout(workspace, p->n, p->S);
+  if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
+  for (int i = 0; i < 5; ++i)
+    if (overlaps(vec[i], nb, workspace, w.bytes)) return CO2_EINVAL;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  co2::SweepArgs g{};
+  g.x = params; g.a_in = anchor; g.a_out = anchor_out; g.m = momentum; g.d = dptr;
+  g.dout = delta_out; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
+  g.alpha = p->alpha; g.beta = p->beta; g.phi = p->clip_phi;
+  g.rK = static_cast<float>(1.0 / static_cast<double>(p->K));
+  g.part_m = w.carry_part[0]; g.part_d = w.carry_part[1];
+  const bool has_x = params != nullptr;
+  hipError_t e;
+
+  if (first) {
+    if (p->ev_sweep_begin && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_begin), st)) != hipSuccess)
+      return fail_hip(e);
+    if ((e = co2::launch_first_round(has_x, g, st)) != hipSuccess) return fail_hip(e);
+    if (p->ev_sweep_end && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_end), st)) != hipSuccess)
+      return fail_hip(e);
+    return CO2_OK;
+  }
+
+  // ---- the two sums of squares of Eq. 3, then Lambda per segment
+  const bool need_d0 = first_step_norm == nullptr;
+  if (carried) {
+    e = co2::launch_lambda_stage2(w.carry_part[0], w.carry_part[1], p->seg_off_dev, p->S,
+                                  co2::kSweepTile, first_step_norm, p->penalty_c, p->alpha,
+                                  p->tau, w.seg_sq, w.inv, lambda_out, st);
+  } else {
+    e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, p->clip_phi,
+                                    need_d0 ? dptr.p[0] : nullptr, 0.0f, p->seg_off_dev, p->S,
+                                    p->n, w.norm_part[0], w.norm_part[1], st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = co2::launch_lambda_stage2(w.norm_part[0], w.norm_part[1], p->seg_off_dev, p->S,
+                                  co2::kNormTile, first_step_norm, p->penalty_c, p->alpha,
+                                  p->tau, w.seg_sq, w.inv, lambda_out, st);
+  }
+  if (e != hipSuccess) return fail_hip(e);
+
+  // ---- the fused sweep
+  if (p->ev_sweep_begin && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_begin), st)) != hipSuccess)
+    return fail_hip(e);
+  if ((e = co2::launch_fused_sweep(p->K, has_x, g, st)) != hipSuccess) return fail_hip(e);
+  if (p->ev_sweep_end && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_end), st)) != hipSuccess)
+    return fail_hip(e);
+  return CO2_OK;
+}
+
+int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t nbuf,
+                          const float* momentum, double* sqnorm_out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  if (!p) return CO2_EINVAL;
+  if (!table_ok(p->n, p->S, p->seg_off) || !p->seg_off_dev || !aligned16(p->seg_off_dev))
+    return CO2_EINVAL;
+  if (nbuf < 0 || nbuf > CO2_MAX_NORM_BUFS || (nbuf > 0 && !bufs)) return CO2_EINVAL;
+  if (nbuf == 0 && !momentum) return CO2_EINVAL;
+  if (momentum && !(p->clip_phi > 0.0f)) return CO2_EINVAL;
+  if (!sqnorm_out || !aligned16(sqnorm_out) || !aligned16(momentum)) return CO2_EINVAL;
+  const size_t nb = sizeof(float) * static_cast<size_t>(p->n);
+  const int rows = nbuf + (momentum ? 1 : 0);
+  const size_t ob = sizeof(double) * static_cast<size_t>(rows) * static_cast<size_t>(p->S);
+  const Workspace w = layout(workspace, p->n, p->S);
+  if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
+  if (overlaps(sqnorm_out, ob, workspace, w.bytes) || overlaps(sqnorm_out, ob, momentum, nb))
+    return CO2_EINVAL;
+  for (int i = 0; i < nbuf; ++i) {
+    if (!bufs[i] || !aligned16(bufs[i]) || overlaps(bufs[i], nb, sqnorm_out, ob) ||
+        overlaps(bufs[i], nb, workspace, w.bytes))
+      return CO2_EINVAL;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // Rows are reduced two at a time (two read streams per launch); launches on
+  // one stream run in order, so the partial slots can be reused.
+  for (int r = 0; r < rows; r += 2) {
+    const bool pair = r + 1 < rows;
+    const float* b0 = r < nbuf ? bufs[r] : momentum;
+    const float phi0 = r < nbuf ? 0.0f : p->clip_phi;
+    const float* b1 = pair ? (r + 1 < nbuf ? bufs[r + 1] : momentum) : nullptr;
+    const float phi1 = pair ? (r + 1 < nbuf ? 0.0f : p->clip_phi) : 0.0f;
+    hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, p->seg_off_dev,
+                                               p->S, p->n, w.norm_part[0], w.norm_part[1], st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = co2::launch_segment_totals(w.norm_part[0], p->seg_off_dev, p->S, co2::kNormTile,
+                                   sqnorm_out + static_cast<size_t>(r) * p->S, st);
+    if (e != hipSuccess) return fail_hip(e);
+    if (pair) {
+      e = co2::launch_segment_totals(w.norm_part[1], p->seg_off_dev, p->S, co2::kNormTile,
+                                     sqnorm_out + static_cast<size_t>(r + 1) * p->S, st);
+      if (e != hipSuccess) return fail_hip(e);
+    }
+  }
+  return CO2_OK;
+}
+
+int co2_inner_adamw(int64_t n, const float* p_in, float* p_out, const uint16_t* grad_bf16,
+                    float* exp_avg, float* exp_avg_sq, float lr, float beta1, float beta2,
+                    float eps, float weight_decay, int64_t adam_step, const float* anchor,
+                    float* delta_out, const int64_t* seg_off, const int64_t* seg_off_dev,
+                    int32_t S, double* step_sq_out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  if (n < 1 || !p_in || !p_out || !grad_bf16 || !exp_avg || !exp_avg_sq) return CO2_EINVAL;
+  if (adam_step < 1) return CO2_EINVAL;
+  if (!std::isfinite(lr) || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) ||
+      !(eps >= 0.0f) || !std::isfinite(weight_decay))
+    return CO2_EINVAL;
+  if ((anchor == nullptr) != (delta_out == nullptr)) return CO2_EINVAL;
+  const bool want_norm = step_sq_out != nullptr;
+  if (want_norm != (seg_off_dev != nullptr) || want_norm != (seg_off != nullptr) ||
+      want_norm != (S != 0))
+    return CO2_EINVAL;
+  if (want_norm && !table_ok(n, S, seg_off)) return CO2_EINVAL;
+  const size_t nb = sizeof(float) * static_cast<size_t>(n);
+  const void* outs[4] = {p_out, exp_avg, exp_avg_sq, delta_out};
+  const size_t outb[4] = {nb, nb, nb, nb};
+  const void* ins[3] = {grad_bf16, anchor, p_in == p_out ? nullptr : p_in};
+  const size_t inb[3] = {nb / 2, nb, nb};
+  for (int i = 0; i < 4; ++i) {
+    if (!aligned16(outs[i])) return CO2_EINVAL;
+    for (int j = i + 1; j < 4; ++j)
+      if (overlaps(outs[i], outb[i], outs[j], outb[j])) return CO2_EINVAL;
+    for (int j = 0; j < 3; ++j)
+      if (overlaps(outs[i], outb[i], ins[j], inb[j])) return CO2_EINVAL;
+  }
+  if (!aligned16(p_in) || !aligned16(grad_bf16) || !aligned16(anchor) ||
+      !aligned16(seg_off_dev) || !aligned16(step_sq_out))
+    return CO2_EINVAL;
+  Workspace w{};
+  if (want_norm) {
+    w = layout(workspace, n, S);
+    if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
+    for (int i = 0; i < 4; ++i)
+      if (overlaps(outs[i], outb[i], workspace, w.bytes) ||
+          overlaps(outs[i], outb[i], step_sq_out, sizeof(double) * static_cast<size_t>(S)))
+        return CO2_EINVAL;
+  }
+
+  // Scalars of the step, evaluated once on the host in fp64 and rounded to fp32.
+  const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(adam_step));
+  const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(adam_step));
+  co2::AdamArgs g{};
+  g.n = n; g.p_in = p_in; g.p_out = p_out; g.grad = grad_bf16;
+  g.exp_avg = exp_avg; g.exp_avg_sq = exp_avg_sq;
+  g.beta1 = beta1; g.beta2 = beta2; g.omb1 = 1.0f - beta1; g.omb2 = 1.0f - beta2;
+  g.decay = 1.0f - lr * weight_decay;
+  g.step_size = static_cast<float>(static_cast<double>(lr) / bc1);
+  g.sqrt_bc2 = static_cast<float>(std::sqrt(bc2));
+  g.eps = eps;
+  g.anchor = anchor; g.dout = delta_out;
+  g.off_dev = seg_off_dev; g.S = S; g.part = want_norm ? w.adam_part : nullptr;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = co2::launch_adamw(g, st);
+  if (e != hipSuccess) return fail_hip(e);
+  if (want_norm) {
+    e = co2::launch_segment_totals(w.adam_part, seg_off_dev, S, co2::kAdamTile, step_sq_out, st);
+    if (e != hipSuccess) return fail_hip(e);
+  }
+  return CO2_OK;
+}
+
+int co2_sqrt_to_f32(const double* sq, float* out, int32_t S, void* hip_stream) {
+  if (!sq || !out || S < 1 || !aligned16(sq) || !aligned16(out)) return CO2_EINVAL;
+  if (overlaps(sq, sizeof(double) * static_cast<size_t>(S), out, sizeof(float) * static_cast<size_t>(S)))
+    return CO2_EINVAL;
+  hipError_t e = co2::launch_sqrt_to_f32(sq, out, S, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? CO2_OK : fail_hip(e);
+}
+
+int co2_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream) {
+  if (!src || !dst || n < 1 || !aligned16(src) || !aligned16(dst)) return CO2_EINVAL;
+  const size_t nb = sizeof(float) * static_cast<size_t>(n);
+  if (overlaps(src, nb, dst, nb)) return CO2_EINVAL;
+  hipError_t e = co2::launch_copy_f32(src, dst, n, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? CO2_OK : fail_hip(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,208 @@
+"""Test harness: drives the HIP library and the CPU oracle over the same seeded
+workload, each carrying its own state, and compares them.
+
+The device side holds the whole workload (3 + K + 1 flat buffers).  The oracle
+side holds only a sample of whole segments (segments are independent in the
+update, so a subset of them is itself a valid, smaller problem), gathered into
+contiguous host arrays with a compact segment table.  Inputs that both sides
+consume (initial state, per-round drift of the local worker, peers'
+pseudo-gradients) are produced by co2_inputs on the device and copied to the
+host; nothing the HIP library computes is ever fed to the oracle.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import co2_inputs
+import paper_2401_16265_amd as co2
+from oracle import co2_oracle
+
+REL_TOL = 1e-5       # spec tolerance, fp32 path vs fp32-ordered oracle
+TRUTH_TOL = 1e-5     # vs the all-fp64 oracle, relative to the operands of each sum
+
+
+@dataclass
+class HP:
+    K: int
+    alpha: float = 1.0
+    beta: float = 0.9
+    phi: float = 1.0
+    c: float = 1.0
+    tau: int = 4
+
+
+def rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """max |got - want| / |want| over elements (0/0 counts as 0)."""
+    g, w = got.astype(np.float64), want.astype(np.float64)
+    diff = np.abs(g - w)
+    den = np.abs(w)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.where(diff == 0, 0.0, diff / den)
+    return float(r.max()) if r.size else 0.0
+
+
+def assert_close(got, want, what, tol=REL_TOL):
+    e = rel_err(np.asarray(got), np.asarray(want))
+    assert e <= tol, f"{what}: max relative error {e:.3e} > {tol:g}"
+    return e
+
+
+class OuterStepHarness:
+    def __init__(self, table: Sequence[int], hp: HP, device, seed: int = 0,
+                 sample: Optional[Sequence[int]] = None, drift: str = "normal",
+                 drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
+                 momentum_std: float = 0.02, truth: bool = False, use_first_step_norm: bool = False,
+                 start_step: int = 0):
+        self.table = list(table)
+        self.n, self.S = self.table[-1], len(self.table) - 1
+        self.hp, self.dev, self.seed = hp, device, seed
+        self.drift, self.drift_scale, self.drift_nu = drift, drift_scale, drift_nu
+        self.seg = co2.SegmentTable(self.table, device)
+        n, K = self.n, hp.K
+        f32 = dict(dtype=torch.float32, device=device)
+        self.x = torch.empty(n, **f32)
+        self.a = torch.empty(n, **f32)
+        self.m = torch.empty(n, **f32)
+        self.own = [torch.zeros(n, **f32), torch.zeros(n, **f32)]   # ping-pong: delta_out / deltas[0]
+        self.peers = [torch.zeros(n, **f32) for _ in range(K - 1)]
+        self.lam = torch.empty(self.S, **f32)
+        self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
+        self.fsn = None
+        if use_first_step_norm:
+            self.fsn = torch.empty(self.S, **f32)
+        co2_inputs.fill_normal_(self.a, param_std, co2_inputs.seed_for(seed, 1))
+        if momentum_std > 0:
+            co2_inputs.fill_normal_(self.m, momentum_std, co2_inputs.seed_for(seed, 2))
+        else:
+            self.m.zero_()
+        self.t = start_step
+
+        # ---- oracle side: sampled segments, compact table
+        self.sample = list(range(self.S)) if sample is None else sorted(set(sample))
+        sizes = [self.table[s + 1] - self.table[s] for s in self.sample]
+        self.otable = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        self.o_a = self.gather(self.a)
+        self.o_m = self.gather(self.m)
+        self.o_x = np.empty_like(self.o_a)
+        self.o_own = np.zeros_like(self.o_a)
+        if start_step >= 1:
+            # no earlier round has produced the worker's own previous
+            # pseudo-gradient: draw it like a peer's
+            self._fill_drift(self.own[start_step % 2], 99)
+            self.o_own = self.gather(self.own[start_step % 2])
+        self.truth = truth
+        if truth:
+            self.t_a, self.t_m = self.o_a.astype(np.float64), self.o_m.astype(np.float64)
+            self.t_own = self.o_own.astype(np.float64)
+
+    # -- helpers
+    def gather(self, buf: torch.Tensor) -> np.ndarray:
+        parts = [buf[self.table[s]:self.table[s + 1]] for s in self.sample]
+        if len(parts) == 1:
+            return parts[0].cpu().numpy().copy()
+        return torch.cat(parts).cpu().numpy()
+
+    def _fill_drift(self, t: torch.Tensor, buffer_id: int):
+        sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)
+        if self.drift == "student_t":
+            co2_inputs.fill_student_t_(t, self.drift_scale, self.drift_nu, sd)
+        else:
+            co2_inputs.fill_normal_(t, self.drift_scale, sd)
+
+    def step(self, flags: int = 0, split: bool = False, check: bool = True, events=None):
+        """One outer round on both sides; returns dict of worst relative errors."""
+        hp, t = self.hp, self.t
+        cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]   # cur: deltas[0]; nxt: delta_out
+        # inner loop stand-in: local params drift away from the anchor
+        self._fill_drift(nxt, 100)                      # scratch: overwritten by delta_out
+        torch.add(self.a, nxt, out=self.x)
+        o_noise = self.gather(nxt)
+        self.o_x = self.o_a + o_noise                   # same fp32 add as the line above
+        # peers' pseudo-gradients of the previous round (arrived through the all-reduce)
+        o_peers = []
+        if t >= 1:
+            for k, pbuf in enumerate(self.peers):
+                self._fill_drift(pbuf, 200 + k)
+                o_peers.append(self.gather(pbuf))
+        if self.fsn is not None:
+            co2_inputs.fill_normal_(self.fsn, 1.0, co2_inputs.seed_for(self.seed, 300, t))
+            self.fsn.abs_().mul_(self.drift_scale * 10).add_(self.drift_scale)
+        o_fsn = None if self.fsn is None else self.fsn[self.sample].cpu().numpy().copy()
+
+        # ---- device
+        ev_b, ev_e = events if events else (None, None)
+        p = co2.make_params(self.seg, hp.K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
+                            ev_b, ev_e)
+        deltas = [cur] + self.peers
+        a_out = self.a
+        if split:
+            # side-stream form: m and the next anchor only; the boundary work
+            # (delta_out, params) is done by the caller
+            a_out = torch.empty_like(self.a)
+            co2.co2_outer_step(p, None, self.a, a_out, self.m, deltas, None, self.fsn, self.lam,
+                               self.ws)
+            torch.sub(self.a, self.x, out=nxt)
+            self.x.copy_(a_out)
+            self.a.copy_(a_out)
+        else:
+            co2.co2_outer_step(p, self.x, self.a, self.a, self.m, deltas, nxt, self.fsn, self.lam,
+                               self.ws)
+
+        # ---- oracle
+        kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
+                  tau=hp.tau, step=t)
+        o_d = [self.o_own] + o_peers if t >= 1 else None
+        out = co2_oracle.outer_step_f32(x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d,
+                                        first_step_norm=o_fsn, **kw)
+        self.o_own = out["dout"]
+        self.last = out
+        res = {}
+        if self.truth:
+            t_x = self.t_a + o_noise.astype(np.float64)
+            t_d = [self.t_own] + [v.astype(np.float64) for v in o_peers] if t >= 1 else None
+            self._truth_prev = (self.t_a.copy(), self.t_m.copy(), t_d)
+            tout = co2_oracle.outer_step_f64(x=t_x, a=self.t_a, m=self.t_m, deltas=t_d,
+                                             first_step_norm=None if o_fsn is None else o_fsn.astype(np.float64),
+                                             **kw)
+            self.t_own = tout["dout"]
+            self.last_truth = tout
+        self.last_step = t
+        self.t += 1
+        if check:
+            res = self.compare(nxt)
+        return res
+
+    def compare(self, dout_buf: torch.Tensor):
+        """Element-by-element comparison of every output on the sampled segments."""
+        res = {}
+        g_x, g_a, g_m, g_d = (self.gather(b) for b in (self.x, self.a, self.m, dout_buf))
+        res["params"] = assert_close(g_x, self.o_x, "params")
+        res["anchor"] = assert_close(g_a, self.o_a, "anchor")
+        res["momentum"] = assert_close(g_m, self.o_m, "momentum")
+        res["delta_out"] = assert_close(g_d, self.o_own, "delta_out")
+        res["bit_exact"] = bool(np.array_equal(g_x, self.o_x) and np.array_equal(g_m, self.o_m)
+                                and np.array_equal(g_d, self.o_own) and np.array_equal(g_a, self.o_a))
+        if self.last_step >= 1:
+            g_lam = self.lam[self.sample].cpu().numpy()
+            res["lambda"] = assert_close(g_lam, self.last["lam"], "Lambda")
+        if self.truth and self.last_step >= 1:
+            # against the all-fp64 evaluation: a sum is only accurate relative to
+            # the size of its operands (beta*m and dbar/Lambda nearly cancel on a
+            # few percent of coordinates)
+            hp = self.hp
+            a_prev, m_prev, t_d = self._truth_prev
+            lam = np.repeat(self.last_truth["lam"], np.diff(self.otable))
+            dbar = np.mean(t_d, axis=0)
+            scale_m = np.abs(hp.beta * m_prev) + np.abs(dbar / lam)
+            bad = np.abs(g_m - self.t_m) > TRUTH_TOL * scale_m + 1e-30
+            assert not bad.any(), f"momentum vs fp64 truth: {int(bad.sum())} coordinates off"
+            scale_x = np.abs(a_prev) + hp.alpha * np.abs(np.clip(self.t_m, -hp.phi, hp.phi))
+            bad = np.abs(g_a - self.t_a) > TRUTH_TOL * scale_x + 1e-30
+            assert not bad.any(), f"anchor vs fp64 truth: {int(bad.sum())} coordinates off"
+            res["lambda_vs_truth"] = assert_close(self.lam[self.sample].cpu().numpy(),
+                                                  self.last_truth["lam"], "Lambda vs truth")
+        return res

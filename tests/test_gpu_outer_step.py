@@ -1,0 +1,222 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.
+
+Tolerance (written here, derived in the design document): every element of
+every output within 1e-5 relative of the fp32-ordered oracle; Lambda and the
+norms within 1e-5 relative; and, where the harness also carries the all-fp64
+evaluation, within 1e-5 of it relative to the operands of each sum.  Both sides
+evaluate the same unfused fp32 expression, so bit equality is the usual outcome
+and is reported, but the assertion is the tolerance.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import co2_inputs
+import paper_2401_16265_amd as co2
+from harness import HP, OuterStepHarness, assert_close
+
+pytestmark = pytest.mark.gpu
+INF = float("inf")
+
+
+@pytest.fixture()
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    d = torch.device("cuda:0")
+    yield d
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def run_steps(h, steps, **kw):
+    out = []
+    for _ in range(steps):
+        print(f"  outer step t={h.t} n={h.n} S={h.S} K={h.hp.K} {kw}", flush=True)
+        out.append(h.step(**kw))
+    torch.cuda.synchronize()
+    return out
+
+
+# ------------------------------------------------------------------ config 1
+def test_tiny_config(dev):
+    cfg = co2_inputs.CONFIGS["tiny"]
+    table = co2_inputs.config_table(cfg)
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, momentum_std=cfg.momentum_std,
+                         truth=True, start_step=1)
+    res = run_steps(h, 1)[0]
+    assert res["lambda"] <= 1e-5 and np.all(h.last["lam"] > 1.0)
+    print("tiny:", res)
+
+
+def test_tiny_config_heavy_clipping(dev):
+    cfg = co2_inputs.CONFIGS["tiny"]
+    table = co2_inputs.config_table(cfg)
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=1e-3, c=cfg.c, tau=cfg.tau)
+    h = OuterStepHarness(table, hp, dev, seed=3, momentum_std=0.02, truth=True, start_step=1)
+    run_steps(h, 2)
+    assert h.last["nclipped"] > h.n // 2
+    # clipped coordinates moved by exactly alpha*phi
+    moved = np.abs(h.gather(h.a).astype(np.float64) - h._truth_prev[0])
+    assert moved.max() <= hp.alpha * hp.phi * (1 + 1e-4)
+
+
+# ------------------------------------------------------------------ edge shapes
+EDGE_TABLES = {
+    "one_element": [0, 1],
+    "five_two_segments": [0, 2, 5],
+    "per_coordinate_1023": list(range(0, 1024)),
+    "global_4097": [0, 4097],
+    "odd_offsets_empty_segments": [0, 0, 13, 13, 2049, 5000, 5000, 6221],
+    "boundary_at_tile_edges": [0, 2048, 4096, 4096, 8192, 8193, 16384 + 2048],
+    "many_small_then_large": list(range(0, 300, 3)) + [300, 40000],
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_TABLES))
+@pytest.mark.parametrize("K", [1, 2, 3, 8, 16])
+def test_edge_shapes(dev, name, K):
+    h = OuterStepHarness(EDGE_TABLES[name], HP(K=K, beta=0.8, phi=0.01, c=1.0, tau=3), dev,
+                         seed=7, momentum_std=0.02, truth=True)
+    run_steps(h, 3)
+
+
+@pytest.mark.parametrize("K", [4, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15])
+def test_every_worker_count(dev, K):
+    h = OuterStepHarness([0, 77, 5000, 20011], HP(K=K, beta=0.9, phi=0.5, c=1.0), dev, seed=K,
+                         start_step=1)
+    run_steps(h, 1)
+
+
+@pytest.mark.parametrize("hp", [
+    HP(K=4, c=0.0), HP(K=4, phi=INF), HP(K=4, beta=0.0), HP(K=4, alpha=0.25, c=3.0, tau=12),
+    HP(K=1, c=0.0, phi=INF, beta=0.5, alpha=0.7),
+], ids=["no_penalty", "no_clipping", "no_momentum", "alpha_c_tau", "momentum_sgd"])
+def test_hyperparameter_corners(dev, hp):
+    table = co2_inputs.gpt_table(layers=2, d=64, ffn=256, vocab=1001, ctx=32)
+    h = OuterStepHarness(table, hp, dev, seed=11, momentum_std=0.01, truth=True)
+    res = run_steps(h, 3)
+    if hp.c == 0.0:
+        assert np.all(h.lam.cpu().numpy() == 1.0)
+
+
+def test_first_step_norm_supplied(dev):
+    table = co2_inputs.gpt_table(layers=2, d=64, ffn=256, vocab=1001, ctx=32)
+    h = OuterStepHarness(table, HP(K=8, phi=0.02, tau=6), dev, seed=12, truth=True,
+                         use_first_step_norm=True)
+    run_steps(h, 3)
+    assert np.all(h.last["lam"] > 1.0)
+
+
+# ------------------------------------------------------------------ multi-step, all forms
+@pytest.mark.parametrize("mode", ["two_pass", "carried", "split", "split_carried_fsn"])
+def test_multi_step_ragged_table(dev, mode):
+    """Six consecutive rounds from t=0 on a ragged table whose offsets are not
+    multiples of 4 (odd vocabulary), state carried on both sides."""
+    table = co2_inputs.gpt_table(layers=3, d=96, ffn=384, vocab=3001, ctx=64)
+    assert any(o % 4 for o in table)
+    h = OuterStepHarness(table, HP(K=8, beta=0.95, phi=2e-3, c=1.0), dev, seed=21,
+                         momentum_std=0.0, drift="student_t", truth=True,
+                         use_first_step_norm=(mode == "split_carried_fsn"))
+    for t in range(6):
+        flags = co2.CO2_FLAG_CARRIED_NORMS if (mode in ("carried", "split_carried_fsn") and t >= 1) else 0
+        print(f"  {mode} t={t}", flush=True)
+        h.step(flags=flags, split=mode.startswith("split"))
+    assert h.last["nclipped"] > 0
+
+
+def test_carried_norms_equal_two_pass(dev):
+    """The sums left by the sweep give the same Lambda as re-reading m and d0."""
+    table = co2_inputs.gpt_table(layers=2, d=128, ffn=512, vocab=2001, ctx=32)
+    hs = [OuterStepHarness(table, HP(K=4, phi=0.01), dev, seed=5, momentum_std=0.0)
+          for _ in range(2)]
+    for t in range(4):
+        hs[0].step(flags=0)
+        hs[1].step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+        if t >= 1:
+            assert_close(hs[1].lam.cpu().numpy(), hs[0].lam.cpu().numpy(), "Lambda", tol=1e-6)
+        assert torch.equal(hs[0].m, hs[1].m) and torch.equal(hs[0].a, hs[1].a)
+
+
+# ------------------------------------------------------------------ norms entry point
+def test_pseudo_grad_norms(dev, oracle):
+    table = [0, 0, 13, 2049, 8192, 8193, 70001]
+    seg = co2.SegmentTable(table, dev)
+    n, S = seg.n, seg.S
+    g = torch.Generator(device=dev); g.manual_seed(5)
+    bufs = [torch.randn(n, device=dev, generator=g) * (0.1 * (i + 1)) for i in range(5)]
+    mom = torch.randn(n, device=dev, generator=g)
+    ws = torch.empty(co2.workspace_bytes(n, S, 1), dtype=torch.uint8, device=dev)
+    p = co2.make_params(seg, 1, 1.0, 0.9, 0.5, 1.0, 1, 0)
+    for nb, use_m in [(5, True), (3, False), (0, True), (1, False), (2, True)]:
+        rows = nb + (1 if use_m else 0)
+        out = torch.full((rows, S), -1.0, dtype=torch.float64, device=dev)
+        co2.co2_pseudo_grad_norms(p, bufs[:nb], mom if use_m else None, out, ws)
+        got = out.cpu().numpy()
+        for i in range(nb):
+            assert_close(got[i], oracle.sqnorms(bufs[i].cpu().numpy(), table), f"buffer {i}", tol=1e-12)
+        if use_m:
+            assert_close(got[nb], oracle.sqnorms(mom.cpu().numpy(), table, phi=0.5), "momentum", tol=1e-12)
+    # determinism: same bits on a second call
+    out2 = torch.empty_like(out)
+    co2.co2_pseudo_grad_norms(p, bufs[:2], mom, out2, ws)
+    assert torch.equal(out, out2)
+
+
+# ------------------------------------------------------------------ config 2, full size
+def test_gpt2_small_ten_steps(dev):
+    cfg = co2_inputs.CONFIGS["gpt2s"]
+    table = co2_inputs.config_table(cfg)
+    assert table[-1] == 124_439_808 and len(table) - 1 == 148
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    # every segment of layers 0 and 11, both embeddings and the final norm
+    sample = [0, 1] + list(range(2, 14)) + list(range(134, 148))
+    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift_scale=cfg.drift_scale,
+                         momentum_std=cfg.momentum_std, start_step=1)
+    res = run_steps(h, cfg.steps)
+    print("gpt2s last step:", res[-1])
+
+
+# ------------------------------------------------------------------ config 3, headline size
+def test_1p3b_headline_size_sampled(dev):
+    """Full 1.34B-parameter buffers, K=8, Student-t drift, in the launch
+    configuration the bench times (carried norms after the first two rounds);
+    outputs checked on a sample of whole segments that includes the largest
+    (131M elements), the smallest, and segments from the first/middle/last layers."""
+    cfg = co2_inputs.CONFIGS["1p3b"]
+    table = co2_inputs.config_table(cfg)
+    assert table[-1] == 1_343_868_928 and len(table) - 1 == 292
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    sample = [0, 1, 2, 3, 4, 5, 10, 11, 150, 151, 152, 286, 287, 288, 289, 290, 291]
+    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift="student_t",
+                         drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
+                         momentum_std=cfg.momentum_std, start_step=1)
+    for t in range(4):
+        flags = co2.CO2_FLAG_CARRIED_NORMS if t >= 2 else 0
+        print(f"  1p3b step {h.t} flags={flags}", flush=True)
+        res = h.step(flags=flags)
+        print("   ", res, "nclipped(sample)=", h.last["nclipped"], flush=True)
+    # Lambda of ALL segments against oracle norms of the full momentum / own delta
+    # buffers is covered per sampled segment above; here: every Lambda >= 1
+    lam = h.lam.cpu().numpy()
+    assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
+
+
+# ------------------------------------------------------------------ config 4, ZeRO-style shard
+@pytest.mark.parametrize("rank", [1, 0])
+def test_7b_shard_partial_segments(dev, rank):
+    cfg = co2_inputs.CONFIGS["7b_shard"]
+    table = co2_inputs.config_table(cfg, rank=rank)
+    assert table[-1] == 421_150_976
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    S = len(table) - 1
+    sample = sorted({0, 1, 2, S // 2, S - 2, S - 1})       # first and last are partial tensors
+    h = OuterStepHarness(table, hp, dev, seed=cfg.seed + rank, sample=sample,
+                         drift_scale=cfg.drift_scale, momentum_std=cfg.momentum_std, start_step=1)
+    for t in range(3):
+        print(f"  7b shard rank {rank} step {h.t}", flush=True)
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+    print("7b shard:", res)

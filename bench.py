@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the CO2 outer update on one MI355X.
+
+A "step" is one pass of the whole outer update (pseudo-gradient, K-way mean,
+the two segment norms and Lambda of Eq. 3, momentum, clipping, outer iterate,
+writes of params/anchor/momentum/delta_out) over the 1.3B-parameter, K=8
+workload, with every buffer already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--form carried|two_pass]
+                  [--workload 1p3b|gpt2s|7b_shard|tiny] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per launch of the fused sweep measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel calibration);
+# summaries under profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--form", choices=["carried", "two_pass"], default="carried",
+                    help="carried: steady-state single pass (norm sums carried from the "
+                         "previous round's sweep); two_pass: separate norm pass every round")
+    ap.add_argument("--workload", default="1p3b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, table, sample_elems: int, gen_device="cpu"):
+    """The oracle, as it stands, single-threaded on this host, on a bounded sample
+    of whole segments of the same workload (same K, same drift recipe)."""
+    import numpy as np
+    import torch
+
+    import co2_inputs
+    from oracle import co2_oracle
+
+    # whole segments, largest-first skipped if too big, until the budget is filled
+    sizes = [table[s + 1] - table[s] for s in range(len(table) - 1)]
+    chosen, total = [], 0
+    for s in range(len(sizes) - 1, -1, -1):          # from the last layers backwards
+        if total + sizes[s] <= sample_elems:
+            chosen.append(s)
+            total += sizes[s]
+    chosen.sort()
+    otable = np.concatenate([[0], np.cumsum([sizes[s] for s in chosen])]).astype(np.int64)
+    n = int(otable[-1])
+
+    def draw(std, bid, student=False):
+        # drawn on the GPU when there is one (the Student-t recipe is slow on the
+        # host), then handed to the oracle as host arrays
+        t = torch.empty(n, dtype=torch.float32, device=gen_device)
+        if student:
+            co2_inputs.fill_student_t_(t, std, cfg.drift_nu, co2_inputs.seed_for(cfg.seed, bid))
+        else:
+            co2_inputs.fill_normal_(t, std, co2_inputs.seed_for(cfg.seed, bid))
+        return t.cpu().numpy()
+
+    st = cfg.drift == "student_t"
+    a = draw(cfg.param_std, 1)
+    m = draw(cfg.momentum_std, 2)
+    x = a + draw(cfg.drift_scale, 100, st)
+    d = [draw(cfg.drift_scale, 200 + k, st) for k in range(cfg.K)]
+    kw = dict(seg_off=otable, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    co2_oracle.outer_step_f32(x=x, a=a, m=m, deltas=d, step=1, **kw)      # warm the pages
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        co2_oracle.outer_step_f32(x=x, a=a, m=m, deltas=d, step=2 + reps, **kw)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > 10.0 or reps >= 8:
+            break
+    return {"value": n * reps / el, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(chosen)} whole segments ({n} of {table[-1]} params) of the same "
+                      f"workload, K={cfg.K}, {reps} outer steps in {el:.1f} s, g++ -O2, 1 thread"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the K workers are K device buffers "
+              "reduced in-kernel); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import co2_inputs
+    import paper_2401_16265_amd as co2
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = co2_inputs.CONFIGS[args.workload]
+    table = co2_inputs.config_table(cfg)
+    seg = co2.SegmentTable(table, dev)
+    n, S, K = seg.n, seg.S, cfg.K
+    f32 = dict(dtype=torch.float32, device=dev)
+
+    # ---- resident state: params, anchor, momentum, K-1 peers, 2 own (ping-pong)
+    a = torch.empty(n, **f32); m = torch.empty(n, **f32); x = torch.empty(n, **f32)
+    own = [torch.empty(n, **f32), torch.empty(n, **f32)]
+    peers = [torch.empty(n, **f32) for _ in range(K - 1)]
+    lam = torch.empty(S, **f32)
+    ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
+    student = cfg.drift == "student_t"
+
+    def drift(t, bid):
+        sd = co2_inputs.seed_for(cfg.seed, bid)
+        if student:
+            co2_inputs.fill_student_t_(t, cfg.drift_scale, cfg.drift_nu, sd)
+        else:
+            co2_inputs.fill_normal_(t, cfg.drift_scale, sd)
+
+    co2_inputs.fill_normal_(a, cfg.param_std, co2_inputs.seed_for(cfg.seed, 1))
+    co2_inputs.fill_normal_(m, cfg.momentum_std, co2_inputs.seed_for(cfg.seed, 2))
+    drift(own[0], 100); torch.add(a, own[0], out=x)
+    drift(own[1], 99)
+    for k, pb in enumerate(peers):
+        drift(pb, 200 + k)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream().cuda_stream
+    carried = args.form == "carried"
+    step_no = [1]
+
+    def one_step(ev=None):
+        t = step_no[0]
+        cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
+        flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
+        p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
+                            ev[0] if ev else None, ev[1] if ev else None)
+        co2.co2_outer_step(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
+        step_no[0] += 1
+
+    warmup = max(args.warmup, 2 if carried else 0)   # carried sums exist from round 2 on
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    events = [(co2.HipEvent(), co2.HipEvent()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    sweep_ms = sum(b.elapsed_ms(e) for b, e in events) / args.steps
+    sweep_bytes = (28 + 4 * K) * n                      # algorithmic bytes of one sweep launch
+    achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
+
+    # ---- yardstick: plain copy kernel over one buffer pair (8 B/element)
+    cb, ce = co2.HipEvent(), co2.HipEvent()
+    co2.co2_copy_f32(own[0], own[1], n, stream=stream)
+    cb.record(stream)
+    for _ in range(5):
+        co2.co2_copy_f32(own[0], own[1], n, stream=stream)
+    ce.record(stream)
+    ce.synchronize()
+    copy_gbps = 8 * n * 5 / (cb.elapsed_ms(ce) * 1e-3) / 1e9
+
+    out = {
+        "metric": "outer-step params/sec",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
+                               f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
+                               f"c={cfg.c}", "form": args.form,
+                   "step_gbps_algorithmic": (28 + 4 * K + (0 if carried else 8)) * n
+                                            / (ms_per_step * 1e-3) / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.form)),
+                     "kernel": "fused_sweep", "kernel_ms": sweep_ms,
+                     "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
+    }
+    del a, m, x, own, peers
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, table, args.cpu_sample_elems, dev)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -95,9 +95,6 @@ class OuterStepHarness:
             self._fill_drift(self.own[start_step % 2], 99)
             self.o_own = self.gather(self.own[start_step % 2])
         self.truth = truth
-        if truth:
-            self.t_a, self.t_m = self.o_a.astype(np.float64), self.o_m.astype(np.float64)
-            self.t_own = self.o_own.astype(np.float64)
 
     # -- helpers
     def gather(self, buf: torch.Tensor) -> np.ndarray:
@@ -152,6 +149,21 @@ class OuterStepHarness:
             co2.co2_outer_step(p, self.x, self.a, self.a, self.m, deltas, nxt, self.fsn, self.lam,
                                self.ws)
 
+        # ---- all-fp64 evaluation of this one round, from the fp32 oracle's state
+        # before the round (rounding errors of earlier rounds are part of that
+        # state, so the bound below is a per-round statement)
+        kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
+                  tau=hp.tau, step=t)
+        if self.truth:
+            self.t_a, self.t_m = self.o_a.astype(np.float64), self.o_m.astype(np.float64)
+            t_x = self.o_x.astype(np.float64)
+            t_d = ([self.o_own.astype(np.float64)] + [v.astype(np.float64) for v in o_peers]
+                   if t >= 1 else None)
+            self._truth_prev = (self.t_a.copy(), self.t_m.copy(), t_d)
+            self.last_truth = co2_oracle.outer_step_f64(
+                x=t_x, a=self.t_a, m=self.t_m, deltas=t_d,
+                first_step_norm=None if o_fsn is None else o_fsn.astype(np.float64), **kw)
+
         # ---- oracle
         kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
                   tau=hp.tau, step=t)
@@ -161,15 +173,6 @@ class OuterStepHarness:
         self.o_own = out["dout"]
         self.last = out
         res = {}
-        if self.truth:
-            t_x = self.t_a + o_noise.astype(np.float64)
-            t_d = [self.t_own] + [v.astype(np.float64) for v in o_peers] if t >= 1 else None
-            self._truth_prev = (self.t_a.copy(), self.t_m.copy(), t_d)
-            tout = co2_oracle.outer_step_f64(x=t_x, a=self.t_a, m=self.t_m, deltas=t_d,
-                                             first_step_norm=None if o_fsn is None else o_fsn.astype(np.float64),
-                                             **kw)
-            self.t_own = tout["dout"]
-            self.last_truth = tout
         self.last_step = t
         self.t += 1
         if check:
@@ -196,8 +199,10 @@ class OuterStepHarness:
             hp = self.hp
             a_prev, m_prev, t_d = self._truth_prev
             lam = np.repeat(self.last_truth["lam"], np.diff(self.otable))
-            dbar = np.mean(t_d, axis=0)
-            scale_m = np.abs(hp.beta * m_prev) + np.abs(dbar / lam)
+            # the mean over workers is itself a cancelling fp32 sum: its operands
+            # are the |d_k|, not the (smaller) mean
+            dabs = np.mean(np.abs(t_d), axis=0)
+            scale_m = np.abs(hp.beta * m_prev) + dabs / lam
             bad = np.abs(g_m - self.t_m) > TRUTH_TOL * scale_m + 1e-30
             assert not bad.any(), f"momentum vs fp64 truth: {int(bad.sum())} coordinates off"
             scale_x = np.abs(a_prev) + hp.alpha * np.abs(np.clip(self.t_m, -hp.phi, hp.phi))

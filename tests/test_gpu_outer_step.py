@@ -116,7 +116,7 @@ def test_first_step_norm_supplied(dev):
 def test_multi_step_ragged_table(dev, mode):
     """Six consecutive rounds from t=0 on a ragged table whose offsets are not
     multiples of 4 (odd vocabulary), state carried on both sides."""
-    table = co2_inputs.gpt_table(layers=3, d=96, ffn=384, vocab=3001, ctx=64)
+    table = co2_inputs.gpt_table(layers=3, d=97, ffn=385, vocab=3001, ctx=63)
     assert any(o % 4 for o in table)
     h = OuterStepHarness(table, HP(K=8, beta=0.95, phi=2e-3, c=1.0), dev, seed=21,
                          momentum_std=0.0, drift="student_t", truth=True,

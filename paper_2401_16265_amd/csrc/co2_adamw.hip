@@ -10,6 +10,8 @@
 
 namespace co2 {
 
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
 struct AdamScalars {
   float beta1, beta2, omb1, omb2, decay, step_size, sqrt_bc2, eps;
 };
@@ -34,39 +36,44 @@ __device__ __forceinline__ float adamw_coord(float p, float g, float& m1, float&
 }
 
 template <bool HAS_DOUT, bool HAS_NORM>
-__global__ __launch_bounds__(kBlock) void adamw_step(
+__global__ __launch_bounds__(kWave) void adamw_step(
     int64_t n, const float* p_in, float* p_out, const uint16_t* __restrict__ grad,
     float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq, AdamScalars h,
     const float* __restrict__ anchor, float* __restrict__ dout,
     const int64_t* __restrict__ off, int S, double* __restrict__ part) {
-  __shared__ double lds[kWavesPerBlock];
-  constexpr int U = 2;
-  constexpr int64_t kTile = kAdamTile;
+  constexpr int U = kAdamU;
   const int64_t tile = blockIdx.x;
-  const int64_t base = tile * kTile;
-  int s_lo = 0;
-  bool one_segment = true;
-  if (HAS_NORM) {
-    s_lo = seg_of(off, S, base);
-    one_segment = base + kTile <= off[s_lo + 1];
-  }
+  const int64_t base = tile * kAdamTile;
+  const int lane = threadIdx.x;
+  const bool full = base + kAdamTile <= n;
 
-  if (base + kTile <= n && one_segment) {
-    float4 vp[U], vm[U], vv[U], va[U];
-    uint2 vg[U];
+  // All loads of the tile first; the segment lookup overlaps with them.
+  float4 vp[U], vm[U], vv[U], va[U];
+  uint2 vg[U];
+  if (full) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t j = base + ((int64_t(u) * kBlock + threadIdx.x) << 2);
+      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
       vp[u] = ld4(p_in + j);
-      vg[u] = *reinterpret_cast<const uint2*>(grad + j);
+      const v2u gb = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(grad + j));
+      vg[u] = make_uint2(gb.x, gb.y);
       vm[u] = ld4(exp_avg + j);
       vv[u] = ld4(exp_avg_sq + j);
       if (HAS_DOUT) va[u] = ld4(anchor + j);
     }
+  }
+  int s_lo = 0;
+  bool one_segment = true;
+  if (HAS_NORM) {
+    s_lo = seg_of(off, S, base);
+    one_segment = base + kAdamTile <= off[s_lo + 1];
+  }
+
+  if (full && one_segment) {
     double acc = 0.0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t j = base + ((int64_t(u) * kBlock + threadIdx.x) << 2);
+      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
       const float pc[4] = {vp[u].x, vp[u].y, vp[u].z, vp[u].w};
       float mc[4] = {vm[u].x, vm[u].y, vm[u].z, vm[u].w};
       float vc[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
@@ -87,17 +94,16 @@ __global__ __launch_bounds__(kBlock) void adamw_step(
       }
     }
     if (HAS_NORM) {
-      const double t = block_sum(acc, lds);
-      if (threadIdx.x == 0) part[tile + s_lo] = t;
+      const double t = wave_sum(acc);
+      if (lane == 0) part[tile + s_lo] = t;
     }
     return;
   }
 
-  // Boundary or ragged tile: one wavefront per segment piece.
-  const int64_t end = (base + kTile < n) ? base + kTile : n;
+  // Boundary or ragged tile: one segment piece after the other.
+  const int64_t end = (base + kAdamTile < n) ? base + kAdamTile : n;
   const int s_hi = HAS_NORM ? seg_of(off, S, end - 1) : 0;
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
-  for (int s = s_lo + wave; s <= s_hi; s += kWavesPerBlock) {
+  for (int s = s_lo; s <= s_hi; ++s) {
     int64_t lo = base, hi = end;
     if (HAS_NORM) {
       lo = off[s] > base ? off[s] : base;
@@ -124,10 +130,11 @@ __global__ __launch_bounds__(kBlock) void adamw_step(
 
 hipError_t launch_adamw(const AdamArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kAdamTile - 1) / kAdamTile);
+  const unsigned lds = throttle_lds_bytes(tuning().adam_waves_per_cu);
   const AdamScalars h{g.beta1, g.beta2, g.omb1, g.omb2, g.decay, g.step_size, g.sqrt_bc2, g.eps};
   const bool has_dout = g.dout != nullptr, has_norm = g.part != nullptr;
 #define CO2_ADAM_LAUNCH(D, N)                                                              \
-  hipLaunchKernelGGL((adamw_step<D, N>), dim3(tiles), dim3(kBlock), 0, st, g.n, g.p_in,    \
+  hipLaunchKernelGGL((adamw_step<D, N>), dim3(tiles), dim3(kWave), lds, st, g.n, g.p_in,   \
                      g.p_out, g.grad, g.exp_avg, g.exp_avg_sq, h, g.anchor, g.dout,        \
                      g.off_dev, g.S, g.part)
   if (has_dout && has_norm) CO2_ADAM_LAUNCH(true, true);

@@ -3,6 +3,7 @@
 // state; every call enqueues on the caller's stream and returns.
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 
 #include "co2.h"
@@ -42,10 +43,16 @@ struct Workspace {
   double* norm_part[2];    // pass-1 partials (kNormTile tiles): clipped momentum, deltas[0]
   double* carry_part[2];   // partials left by the sweep (kSweepTile tiles) for the next round
   double* adam_part;       // partials of the AdamW step norm (kAdamTile tiles)
+  double* sub[2];          // [S*split] sub-sums of each segment's slots
   double* seg_sq;          // [2][S] per-segment sums
   float* inv;              // [S] 1/Lambda
+  int split;               // workgroups sharing one segment's slots
   size_t bytes;
 };
+
+// Large segments have their slots added by kSegSplit workgroups; tables with
+// very many segments (per-coordinate readings) have short segments and use one.
+inline int split_of(int32_t S) { return S <= 4096 ? co2::kSegSplit : 1; }
 
 inline int64_t slots_of(int64_t n, int64_t tile, int32_t S) { return (n + tile - 1) / tile + S; }
 
@@ -66,13 +73,77 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
   w.carry_part[0] = reinterpret_cast<double*>(take(ss));
   w.carry_part[1] = reinterpret_cast<double*>(take(ss));
   w.adam_part = reinterpret_cast<double*>(take(sa));
+  w.split = split_of(S);
+  const size_t sub = sizeof(double) * static_cast<size_t>(S) * static_cast<size_t>(w.split);
+  w.sub[0] = reinterpret_cast<double*>(take(sub));
+  w.sub[1] = reinterpret_cast<double*>(take(sub));
   w.seg_sq = reinterpret_cast<double*>(take(sizeof(double) * 2 * static_cast<size_t>(S)));
   w.inv = reinterpret_cast<float*>(take(sizeof(float) * static_cast<size_t>(S)));
   w.bytes = o;
   return w;
 }
 
+// Stage 2 of the gap: slots -> per-segment sub-sums -> Lambda, 1/Lambda.
+inline hipError_t enqueue_lambda(const Workspace& w, double* const part[2], int64_t tile_elems,
+                                 const co2_params* p, const float* first_step_norm,
+                                 float* lambda_out, hipStream_t st) {
+  const bool need_d0 = first_step_norm == nullptr;
+  hipError_t e = co2::launch_slot_sums(part[0], need_d0 ? part[1] : nullptr, p->seg_off_dev, p->S,
+                                       tile_elems, w.split, w.sub[0], w.sub[1], st);
+  if (e != hipSuccess) return e;
+  return co2::launch_lambda_finish(w.sub[0], w.sub[1], p->S, w.split, first_step_norm,
+                                   p->penalty_c, p->alpha, p->tau, w.seg_sq, w.inv, lambda_out, st);
+}
+
+inline hipError_t enqueue_totals(const Workspace& w, const double* part, int64_t tile_elems,
+                                 const int64_t* off_dev, int32_t S, double* out, hipStream_t st) {
+  hipError_t e = co2::launch_slot_sums(part, nullptr, off_dev, S, tile_elems, w.split, w.sub[0],
+                                       w.sub[1], st);
+  if (e != hipSuccess) return e;
+  return co2::launch_totals_finish(w.sub[0], S, w.split, out, st);
+}
+
+int env_int(const char* name, int fallback) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return fallback;
+  char* endp = nullptr;
+  const long x = std::strtol(v, &endp, 10);
+  if (endp == v || x < 0 || x > 64) return fallback;
+  return static_cast<int>(x);
+}
+
 }  // namespace
+
+namespace co2 {
+
+const Tuning& tuning() {
+  static const Tuning t = [] {
+    Tuning u{};
+    // Keep about 56-64 KB of loads in flight per compute unit: each wavefront
+    // of the sweep holds 1 KB x (3+K) streams.
+    for (int k = 1; k <= CO2_MAX_K; ++k) {
+      int w = (60 * 1024 + 512 * (3 + k)) / (1024 * (3 + k));
+      if (w < 4) w = 4;
+      if (w > 16) w = 16;
+      u.sweep_waves_per_cu[k] = env_int("CO2_SWEEP_WAVES", w);
+    }
+    u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
+    u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 6);
+    u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 6);
+    return u;
+  }();
+  return t;
+}
+
+unsigned throttle_lds_bytes(int waves_per_cu) {
+  if (waves_per_cu <= 0) return 0;
+  if (waves_per_cu < 3) waves_per_cu = 3;           // a workgroup may reserve at most 64 KB
+  unsigned b = static_cast<unsigned>(kLdsPerCu / waves_per_cu);
+  b &= ~255u;
+  return b > 65536u ? 65536u : b;
+}
+
+}  // namespace co2
 
 extern "C" {
 
@@ -164,17 +235,13 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   // ---- the two sums of squares of Eq. 3, then Lambda per segment
   const bool need_d0 = first_step_norm == nullptr;
   if (carried) {
-    e = co2::launch_lambda_stage2(w.carry_part[0], w.carry_part[1], p->seg_off_dev, p->S,
-                                  co2::kSweepTile, first_step_norm, p->penalty_c, p->alpha,
-                                  p->tau, w.seg_sq, w.inv, lambda_out, st);
+    e = enqueue_lambda(w, w.carry_part, co2::kSweepTile, p, first_step_norm, lambda_out, st);
   } else {
     e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, p->clip_phi,
                                     need_d0 ? dptr.p[0] : nullptr, 0.0f, p->seg_off_dev, p->S,
                                     p->n, w.norm_part[0], w.norm_part[1], st);
     if (e != hipSuccess) return fail_hip(e);
-    e = co2::launch_lambda_stage2(w.norm_part[0], w.norm_part[1], p->seg_off_dev, p->S,
-                                  co2::kNormTile, first_step_norm, p->penalty_c, p->alpha,
-                                  p->tau, w.seg_sq, w.inv, lambda_out, st);
+    e = enqueue_lambda(w, w.norm_part, co2::kNormTile, p, first_step_norm, lambda_out, st);
   }
   if (e != hipSuccess) return fail_hip(e);
 
@@ -221,12 +288,12 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
     hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, p->seg_off_dev,
                                                p->S, p->n, w.norm_part[0], w.norm_part[1], st);
     if (e != hipSuccess) return fail_hip(e);
-    e = co2::launch_segment_totals(w.norm_part[0], p->seg_off_dev, p->S, co2::kNormTile,
-                                   sqnorm_out + static_cast<size_t>(r) * p->S, st);
+    e = enqueue_totals(w, w.norm_part[0], co2::kNormTile, p->seg_off_dev, p->S,
+                       sqnorm_out + static_cast<size_t>(r) * p->S, st);
     if (e != hipSuccess) return fail_hip(e);
     if (pair) {
-      e = co2::launch_segment_totals(w.norm_part[1], p->seg_off_dev, p->S, co2::kNormTile,
-                                     sqnorm_out + static_cast<size_t>(r + 1) * p->S, st);
+      e = enqueue_totals(w, w.norm_part[1], co2::kNormTile, p->seg_off_dev, p->S,
+                         sqnorm_out + static_cast<size_t>(r + 1) * p->S, st);
       if (e != hipSuccess) return fail_hip(e);
     }
   }
@@ -293,7 +360,7 @@ int co2_inner_adamw(int64_t n, const float* p_in, float* p_out, const uint16_t* 
   hipError_t e = co2::launch_adamw(g, st);
   if (e != hipSuccess) return fail_hip(e);
   if (want_norm) {
-    e = co2::launch_segment_totals(w.adam_part, seg_off_dev, S, co2::kAdamTile, step_sq_out, st);
+    e = enqueue_totals(w, w.adam_part, co2::kAdamTile, seg_off_dev, S, step_sq_out, st);
     if (e != hipSuccess) return fail_hip(e);
   }
   return CO2_OK;

@@ -1,5 +1,15 @@
 // Device-side helpers shared by the gfx950 kernels of libco2: launch geometry,
-// wavefront (64-lane) reductions through DPP, segment lookup.
+// wavefront (64-lane) reductions through DPP, segment lookup, streaming
+// loads/stores.
+//
+// Geometry.  Every streaming kernel here runs ONE wavefront per workgroup over
+// an aligned tile of the flat index space, one tile per workgroup, in dispatch
+// order.  On MI355X a mixed read/write stream over many buffers is fastest when
+// each compute unit keeps only about 56-64 KB of loads in flight (5-8
+// wavefronts of 3+K 16-byte loads per lane): more resident wavefronts widen the
+// window of DRAM pages touched at once and cost 10-15 % of HBM bandwidth.  The
+// launch code therefore reserves dynamic LDS per workgroup purely to cap the
+// number of resident wavefronts per compute unit (the kernels never touch it).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -7,21 +17,19 @@
 
 #include "co2.h"
 
-#ifndef CO2_SWEEP_U
-#define CO2_SWEEP_U 2          // 16-byte vectors per lane and stream in the fused sweep
-#endif
-#ifndef CO2_NT
-#define CO2_NT 0               // 1: non-temporal loads/stores on the streaming buffers
-#endif
-
 namespace co2 {
 
-constexpr int kBlock = 256;                       // 4 wavefronts
-constexpr int kWave = 64;
-constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int64_t kNormTile = 8192;               // elements per workgroup, norm pass
-constexpr int64_t kSweepTile = int64_t(kBlock) * 4 * CO2_SWEEP_U;   // fused sweep
-constexpr int64_t kAdamTile = int64_t(kBlock) * 4 * 2;              // AdamW step
+constexpr int kWave = 64;                          // lanes per wavefront = threads per workgroup
+constexpr int kSweepU = 1;                         // 16-byte vectors per lane and stream, fused sweep
+constexpr int kNormU = 4;                          // ... norm pass
+constexpr int kAdamU = 2;                          // ... AdamW step
+constexpr int64_t kSweepTile = int64_t(kWave) * 4 * kSweepU;   // 256 elements
+constexpr int64_t kNormTile = int64_t(kWave) * 4 * kNormU;     // 1024 elements
+constexpr int64_t kAdamTile = int64_t(kWave) * 4 * kAdamU;     // 512 elements
+constexpr int kLdsPerCu = 160 * 1024;              // gfx950 LDS per compute unit
+constexpr int kReduceBlock = 256;                  // threads of the small reduction kernels
+constexpr int kReduceWaves = kReduceBlock / kWave;
+constexpr int kSegSplit = 32;                      // workgroups that share one segment's slots
 
 struct DeltaPtrs {
   const float* p[CO2_MAX_K];
@@ -73,8 +81,8 @@ __device__ __forceinline__ double wave_sum(double v) {
   return ((r0 + r1) + r2) + r3;
 }
 
-// Sum over the workgroup; every thread must call it.  Result valid in all
-// threads.  `lds` holds kWavesPerBlock doubles per concurrent reduction.
+// Sum over a kReduceBlock-thread workgroup (the small reduction kernels only);
+// every thread must call it.  `lds` holds kReduceWaves doubles.
 __device__ __forceinline__ double block_sum(double v, double* lds) {
   const double w = wave_sum(v);
   const int wave = threadIdx.x / kWave;
@@ -83,23 +91,21 @@ __device__ __forceinline__ double block_sum(double v, double* lds) {
   __syncthreads();
   double t = lds[0];
 #pragma unroll
-  for (int i = 1; i < kWavesPerBlock; ++i) t += lds[i];
+  for (int i = 1; i < kReduceWaves; ++i) t += lds[i];
   return t;
 }
 
+// Streaming 16-byte accesses: every element of every buffer is touched once
+// per kernel, so loads and stores carry the non-temporal hint.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float4 ld4(const float* p) {
-#if CO2_NT
-  return __builtin_nontemporal_load(reinterpret_cast<const float4*>(p));
-#else
-  return *reinterpret_cast<const float4*>(p);
-#endif
+  const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
 }
 __device__ __forceinline__ void st4(float* p, float4 v) {
-#if CO2_NT
-  __builtin_nontemporal_store(v, reinterpret_cast<float4*>(p));
-#else
-  *reinterpret_cast<float4*>(p) = v;
-#endif
+  const v4f t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
 }
 
 __device__ __forceinline__ double sq(float v) {

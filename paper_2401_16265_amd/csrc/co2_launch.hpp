@@ -39,13 +39,29 @@ struct AdamArgs {
   double* part;             // per-slot sums of (p' - p_in)^2, nullable
 };
 
+// Resident wavefronts per compute unit each streaming kernel is capped to
+// (0 = no cap).  Defaults come from bandwidth sweeps on MI355X; the environment
+// variables CO2_SWEEP_WAVES, CO2_NORM_WAVES, CO2_ADAM_WAVES and CO2_COPY_WAVES
+// override them (read once, at the first launch) for tuning runs.
+struct Tuning {
+  int sweep_waves_per_cu[CO2_MAX_K + 1];
+  int norm_waves_per_cu;
+  int adam_waves_per_cu;
+  int copy_waves_per_cu;
+};
+const Tuning& tuning();
+// Dynamic LDS bytes to request per single-wavefront workgroup so that at most
+// `waves_per_cu` of them fit on a compute unit.
+unsigned throttle_lds_bytes(int waves_per_cu);
+
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
                                   float phi1, const int64_t* off_dev, int S, int64_t n,
                                   double* part0, double* part1, hipStream_t st);
-hipError_t launch_segment_totals(const double* part, const int64_t* off_dev, int S,
-                                 int64_t tile_elems, double* out, hipStream_t st);
-hipError_t launch_lambda_stage2(const double* part_m, const double* part_d,
-                                const int64_t* off_dev, int S, int64_t tile_elems,
+hipError_t launch_slot_sums(const double* part_a, const double* part_b, const int64_t* off_dev,
+                            int S, int64_t tile_elems, int split, double* out_a, double* out_b,
+                            hipStream_t st);
+hipError_t launch_totals_finish(const double* sub, int S, int split, double* out, hipStream_t st);
+hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S, int split,
                                 const float* first_step_norm, float c, float alpha, int tau,
                                 double* seg_sq, float* inv, float* lambda_out, hipStream_t st);
 hipError_t launch_sqrt_to_f32(const double* sq_in, float* out, int S, hipStream_t st);

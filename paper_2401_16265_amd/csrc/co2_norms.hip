@@ -2,86 +2,84 @@
 // (CO2 paper, Definition 3.1 / Eq. 3) and the per-segment scalar Lambda.
 //
 // Pass 1 (sqnorm_partials): the flat index space is cut into aligned tiles of
-// kNormTile elements, one workgroup each.  A tile that lies inside one segment
-// is read with 16-byte loads, squared and accumulated in fp64 per lane, reduced
-// through DPP + LDS, and leaves ONE partial in slot (tile + segment).  A tile
-// that holds a segment boundary (or the ragged end) gives each of its segments
-// to one wavefront, which leaves one partial per (tile, segment) pair.  The
-// slot index tile+segment is unique per pair because both indices only grow
-// along the flat vector, so no atomics and no zero-fill are needed.
+// kNormTile elements, one single-wavefront workgroup each.  A tile that lies
+// inside one segment is read with 16-byte loads, squared and accumulated in
+// fp64 per lane, reduced across the wavefront through DPP, and leaves ONE
+// partial in slot (tile + segment).  A tile that holds a segment boundary (or
+// the ragged end) walks its segments one after the other and leaves one partial
+// per (tile, segment) pair.  The slot index tile+segment is unique per pair
+// because both indices only grow along the flat vector, so no atomics and no
+// zero-fill are needed.
 //
-// Stage 2 (segment_totals / lambda_stage2): one workgroup per segment adds
-// that segment's slots in a fixed order and, for the outer step, evaluates
-// Lambda in fp64.  Everything is deterministic.
+// Stage 2: slot_sums adds each segment's slots in a fixed order (large segments
+// are split over several workgroups), then lambda_finish / totals_finish adds
+// those few sub-sums in order and, for the outer step, evaluates Lambda in fp64.
+// Everything is deterministic: same inputs, same bits.
 #include "co2_device.hpp"
 #include "co2_launch.hpp"
 
 namespace co2 {
 
+__device__ __forceinline__ void acc4(double& acc, float4 q, float phi) {
+  if (phi > 0.0f) {
+    q.x = clip_coord(q.x, phi); q.y = clip_coord(q.y, phi);
+    q.z = clip_coord(q.z, phi); q.w = clip_coord(q.w, phi);
+  }
+  acc += sq(q.x); acc += sq(q.y); acc += sq(q.z); acc += sq(q.w);
+}
+
 template <int NB>
-__global__ __launch_bounds__(kBlock) void sqnorm_partials(
+__global__ __launch_bounds__(kWave) void sqnorm_partials(
     const float* __restrict__ b0, float phi0, const float* __restrict__ b1, float phi1,
     const int64_t* __restrict__ off, int S, int64_t n,
     double* __restrict__ part0, double* __restrict__ part1) {
-  __shared__ double lds[2][kWavesPerBlock];
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kNormTile;
-  const int64_t end = (base + kNormTile < n) ? base + kNormTile : n;
+  const int lane = threadIdx.x;
+  const bool full = base + kNormTile <= n;
+
+  // Loads first: they do not depend on the segment lookup below, which then
+  // overlaps with them.
+  float4 q0[kNormU], q1[kNormU];
+  if (full) {
+#pragma unroll
+    for (int u = 0; u < kNormU; ++u) {
+      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
+      q0[u] = ld4(b0 + j);
+      if (NB == 2) q1[u] = ld4(b1 + j);
+    }
+  }
   const int s_lo = seg_of(off, S, base);
 
-  if (end <= off[s_lo + 1]) {
-    // Whole tile inside segment s_lo.
+  if (full && base + kNormTile <= off[s_lo + 1]) {
     double a0 = 0.0, a1 = 0.0;
-    const int64_t nvec = (end - base) >> 2;                 // full 16-byte vectors
-    for (int64_t v = threadIdx.x; v < nvec; v += kBlock) {
-      const int64_t j = base + (v << 2);
-      float4 q = ld4(b0 + j);
-      if (phi0 > 0.0f) {
-        q.x = clip_coord(q.x, phi0); q.y = clip_coord(q.y, phi0);
-        q.z = clip_coord(q.z, phi0); q.w = clip_coord(q.w, phi0);
-      }
-      a0 += sq(q.x); a0 += sq(q.y); a0 += sq(q.z); a0 += sq(q.w);
-      if (NB == 2) {
-        float4 r = ld4(b1 + j);
-        if (phi1 > 0.0f) {
-          r.x = clip_coord(r.x, phi1); r.y = clip_coord(r.y, phi1);
-          r.z = clip_coord(r.z, phi1); r.w = clip_coord(r.w, phi1);
-        }
-        a1 += sq(r.x); a1 += sq(r.y); a1 += sq(r.z); a1 += sq(r.w);
-      }
+#pragma unroll
+    for (int u = 0; u < kNormU; ++u) {
+      acc4(a0, q0[u], phi0);
+      if (NB == 2) acc4(a1, q1[u], phi1);
     }
-    for (int64_t j = base + (nvec << 2) + threadIdx.x; j < end; j += kBlock) {   // ragged end
-      float q = b0[j];
-      if (phi0 > 0.0f) q = clip_coord(q, phi0);
-      a0 += sq(q);
-      if (NB == 2) {
-        float r = b1[j];
-        if (phi1 > 0.0f) r = clip_coord(r, phi1);
-        a1 += sq(r);
-      }
-    }
-    const double t0 = block_sum(a0, lds[0]);
+    const double t0 = wave_sum(a0);
     double t1 = 0.0;
-    if (NB == 2) t1 = block_sum(a1, lds[1]);
-    if (threadIdx.x == 0) {
+    if (NB == 2) t1 = wave_sum(a1);
+    if (lane == 0) {
       part0[tile + s_lo] = t0;
       if (NB == 2) part1[tile + s_lo] = t1;
     }
     return;
   }
 
-  // Boundary tile: wavefront w takes segments s_lo+w, s_lo+w+4, ...
+  // Boundary or ragged tile: one segment piece after the other.
+  const int64_t end = (base + kNormTile < n) ? base + kNormTile : n;
   const int s_hi = seg_of(off, S, end - 1);
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
-  for (int s = s_lo + wave; s <= s_hi; s += kWavesPerBlock) {
+  for (int s = s_lo; s <= s_hi; ++s) {
     const int64_t lo = off[s] > base ? off[s] : base;
     const int64_t hi = off[s + 1] < end ? off[s + 1] : end;
-    if (lo >= hi) continue;                                  // empty segment: no slot is read
+    if (lo >= hi) continue;                                  // empty segment: its slot is never read
     double a0 = 0.0, a1 = 0.0;
     for (int64_t j = lo + lane; j < hi; j += kWave) {
-      float q = b0[j];
-      if (phi0 > 0.0f) q = clip_coord(q, phi0);
-      a0 += sq(q);
+      float v = b0[j];
+      if (phi0 > 0.0f) v = clip_coord(v, phi0);
+      a0 += sq(v);
       if (NB == 2) {
         float r = b1[j];
         if (phi1 > 0.0f) r = clip_coord(r, phi1);
@@ -98,107 +96,130 @@ __global__ __launch_bounds__(kBlock) void sqnorm_partials(
   }
 }
 
-// Sum of segment s's slots, in a fixed order; every thread of the block calls.
-__device__ __forceinline__ double segment_total(const double* __restrict__ part, int s,
-                                                int64_t lo, int64_t hi, int64_t tile_elems,
-                                                double* lds) {
-  double acc = 0.0;
-  if (hi > lo) {
-    const int64_t t0 = lo / tile_elems, t1 = (hi - 1) / tile_elems;
-    for (int64_t t = t0 + threadIdx.x; t <= t1; t += kBlock) acc += part[t + s];
-  }
-  return block_sum(acc, lds);
-}
-
-__global__ __launch_bounds__(kBlock) void segment_totals(
-    const double* __restrict__ part, const int64_t* __restrict__ off, int S,
-    int64_t tile_elems, double* __restrict__ out) {
-  __shared__ double lds[kWavesPerBlock];
-  for (int s = blockIdx.x; s < S; s += gridDim.x) {
-    const double t = segment_total(part, s, off[s], off[s + 1], tile_elems, lds);
-    if (threadIdx.x == 0) out[s] = t;
-  }
-}
-
-// Lambda_t per segment (Algorithm 1, gap update; Eq. 3), fp64:
-//   numerator   alpha*sqrt(M2),  M2 = sum Clip(m_{t-1},phi)^2   (slots part_m)
-//   denominator tau*first_step_norm[s], or sqrt(P2), P2 = sum d_0^2 (slots part_d)
-//   Lambda = (c == 0 || T == 0) ? 1 : (c*alpha)*sqrt(M2)/T + 1;  inv = (float)(1/Lambda)
-__global__ __launch_bounds__(kBlock) void lambda_stage2(
-    const double* __restrict__ part_m, const double* __restrict__ part_d,
-    const int64_t* __restrict__ off, int S, int64_t tile_elems,
-    const float* __restrict__ first_step_norm, float c, float alpha, int tau,
-    double* __restrict__ seg_sq, float* __restrict__ inv, float* __restrict__ lambda_out) {
-  __shared__ double lds[2][kWavesPerBlock];
+// Sub-sum g of `split` over segment s's slots (tiles t0..t1 of the producing
+// kernel), in a fixed order.  grid = (segments, split); out[q][s*split + g].
+__global__ __launch_bounds__(kReduceBlock) void slot_sums(
+    const double* __restrict__ part_a, const double* __restrict__ part_b,
+    const int64_t* __restrict__ off, int S, int64_t tile_elems, int split,
+    double* __restrict__ out_a, double* __restrict__ out_b) {
+  __shared__ double lds[2][kReduceWaves];
+  const int g = blockIdx.y;
   for (int s = blockIdx.x; s < S; s += gridDim.x) {
     const int64_t lo = off[s], hi = off[s + 1];
-    const double M2 = segment_total(part_m, s, lo, hi, tile_elems, lds[0]);
-    double P2 = 0.0;
-    if (first_step_norm == nullptr) P2 = segment_total(part_d, s, lo, hi, tile_elems, lds[1]);
-    if (threadIdx.x == 0) {
-      const double T = first_step_norm
-                           ? static_cast<double>(tau) * static_cast<double>(first_step_norm[s])
-                           : sqrt(P2);
-      double Lam = 1.0;
-      if (c != 0.0f && T != 0.0) {
-        Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * sqrt(M2) / T + 1.0;
+    double a = 0.0, b = 0.0;
+    if (hi > lo) {
+      const int64_t t0 = lo / tile_elems, t1 = (hi - 1) / tile_elems;
+      const int64_t chunk = (t1 - t0 + split) / split;       // ceil(count / split)
+      const int64_t c0 = t0 + g * chunk;
+      const int64_t c1 = (c0 + chunk - 1 < t1) ? c0 + chunk - 1 : t1;
+      for (int64_t t = c0 + threadIdx.x; t <= c1; t += kReduceBlock) {
+        a += part_a[t + s];
+        if (part_b) b += part_b[t + s];
       }
-      seg_sq[s] = M2;
-      seg_sq[S + s] = first_step_norm ? T * T : P2;
-      inv[s] = static_cast<float>(1.0 / Lam);
-      if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+    }
+    const double ta = block_sum(a, lds[0]);
+    double tb = 0.0;
+    if (part_b) tb = block_sum(b, lds[1]);
+    if (threadIdx.x == 0) {
+      out_a[int64_t(s) * split + g] = ta;
+      if (part_b) out_b[int64_t(s) * split + g] = tb;
     }
   }
 }
 
-__global__ __launch_bounds__(kBlock) void sqrt_to_f32(const double* __restrict__ sq_in,
-                                                      float* __restrict__ out, int S) {
-  const int s = blockIdx.x * kBlock + threadIdx.x;
+__device__ __forceinline__ double add_in_order(const double* __restrict__ v, int64_t first,
+                                               int count) {
+  double t = v[first];
+  for (int i = 1; i < count; ++i) t += v[first + i];
+  return t;
+}
+
+__global__ __launch_bounds__(kReduceBlock) void totals_finish(
+    const double* __restrict__ sub, int S, int split, double* __restrict__ out) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
+  if (s < S) out[s] = add_in_order(sub, int64_t(s) * split, split);
+}
+
+// Lambda_t per segment (Algorithm 1, gap update; Eq. 3), fp64:
+//   numerator   alpha*sqrt(M2),  M2 = sum Clip(m_{t-1},phi)^2
+//   denominator tau*first_step_norm[s], or sqrt(P2), P2 = sum d_0^2
+//   Lambda = (c == 0 || T == 0) ? 1 : (c*alpha)*sqrt(M2)/T + 1;  inv = (float)(1/Lambda)
+__global__ __launch_bounds__(kReduceBlock) void lambda_finish(
+    const double* __restrict__ sub_m, const double* __restrict__ sub_d, int S, int split,
+    const float* __restrict__ first_step_norm, float c, float alpha, int tau,
+    double* __restrict__ seg_sq, float* __restrict__ inv, float* __restrict__ lambda_out) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
+  if (s >= S) return;
+  const double M2 = add_in_order(sub_m, int64_t(s) * split, split);
+  double P2 = 0.0, T;
+  if (first_step_norm) {
+    T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
+    P2 = T * T;
+  } else {
+    P2 = add_in_order(sub_d, int64_t(s) * split, split);
+    T = sqrt(P2);
+  }
+  double Lam = 1.0;
+  if (c != 0.0f && T != 0.0) {
+    Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * sqrt(M2) / T + 1.0;
+  }
+  seg_sq[s] = M2;
+  seg_sq[S + s] = P2;
+  inv[s] = static_cast<float>(1.0 / Lam);
+  if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+}
+
+__global__ __launch_bounds__(kReduceBlock) void sqrt_to_f32(const double* __restrict__ sq_in,
+                                                            float* __restrict__ out, int S) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
   if (s < S) out[s] = static_cast<float>(sqrt(sq_in[s]));
 }
 
 // ---------------------------------------------------------------- launches
 
-static inline unsigned tiles_of(int64_t n, int64_t tile) {
-  return static_cast<unsigned>((n + tile - 1) / tile);
-}
-
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
                                   float phi1, const int64_t* off_dev, int S, int64_t n,
                                   double* part0, double* part1, hipStream_t st) {
-  const dim3 grid(tiles_of(n, kNormTile)), block(kBlock);
+  const dim3 grid(static_cast<unsigned>((n + kNormTile - 1) / kNormTile)), block(kWave);
+  const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu);
   if (nb == 2) {
-    hipLaunchKernelGGL(sqnorm_partials<2>, grid, block, 0, st, b0, phi0, b1, phi1, off_dev, S, n,
-                       part0, part1);
+    hipLaunchKernelGGL(sqnorm_partials<2>, grid, block, lds, st, b0, phi0, b1, phi1, off_dev, S,
+                       n, part0, part1);
   } else {
-    hipLaunchKernelGGL(sqnorm_partials<1>, grid, block, 0, st, b0, phi0, b0, 0.0f, off_dev, S, n,
-                       part0, part0);
+    hipLaunchKernelGGL(sqnorm_partials<1>, grid, block, lds, st, b0, phi0, b0, 0.0f, off_dev, S,
+                       n, part0, part0);
   }
   return hipGetLastError();
 }
 
-static inline unsigned seg_grid(int S) { return static_cast<unsigned>(S < 65536 ? S : 65536); }
-
-hipError_t launch_segment_totals(const double* part, const int64_t* off_dev, int S,
-                                 int64_t tile_elems, double* out, hipStream_t st) {
-  hipLaunchKernelGGL(segment_totals, dim3(seg_grid(S)), dim3(kBlock), 0, st, part, off_dev, S,
-                     tile_elems, out);
+hipError_t launch_slot_sums(const double* part_a, const double* part_b, const int64_t* off_dev,
+                            int S, int64_t tile_elems, int split, double* out_a, double* out_b,
+                            hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(S < 32768 ? S : 32768), static_cast<unsigned>(split));
+  hipLaunchKernelGGL(slot_sums, grid, dim3(kReduceBlock), 0, st, part_a, part_b, off_dev, S,
+                     tile_elems, split, out_a, out_b);
   return hipGetLastError();
 }
 
-hipError_t launch_lambda_stage2(const double* part_m, const double* part_d,
-                                const int64_t* off_dev, int S, int64_t tile_elems,
+hipError_t launch_totals_finish(const double* sub, int S, int split, double* out,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(totals_finish, dim3((S + kReduceBlock - 1) / kReduceBlock),
+                     dim3(kReduceBlock), 0, st, sub, S, split, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S, int split,
                                 const float* first_step_norm, float c, float alpha, int tau,
                                 double* seg_sq, float* inv, float* lambda_out, hipStream_t st) {
-  hipLaunchKernelGGL(lambda_stage2, dim3(seg_grid(S)), dim3(kBlock), 0, st, part_m, part_d,
-                     off_dev, S, tile_elems, first_step_norm, c, alpha, tau, seg_sq, inv,
-                     lambda_out);
+  hipLaunchKernelGGL(lambda_finish, dim3((S + kReduceBlock - 1) / kReduceBlock),
+                     dim3(kReduceBlock), 0, st, sub_m, sub_d, S, split, first_step_norm, c, alpha,
+                     tau, seg_sq, inv, lambda_out);
   return hipGetLastError();
 }
 
 hipError_t launch_sqrt_to_f32(const double* sq_in, float* out, int S, hipStream_t st) {
-  hipLaunchKernelGGL(sqrt_to_f32, dim3((S + kBlock - 1) / kBlock), dim3(kBlock), 0, st, sq_in,
-                     out, S);
+  hipLaunchKernelGGL(sqrt_to_f32, dim3((S + kReduceBlock - 1) / kReduceBlock),
+                     dim3(kReduceBlock), 0, st, sq_in, out, S);
   return hipGetLastError();
 }
 

@@ -26,7 +26,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per launch of the fused sweep measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel calibration);
 # summaries under profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/fused_sweep_1p3b_k8_hbm_counters.md
+    ("1p3b", "carried"): 8.0967e10,
+}
 
 
 def parse():

@@ -30,8 +30,10 @@ __device__ __forceinline__ float adamw_coord(float p, float g, float& m1, float&
   const float t4 = (h.omb2 * g) * g;
   v = t3 + t4;
   const float pd = p * h.decay;
-  const float denom = __fdiv_rn(__fsqrt_rn(v), h.sqrt_bc2) + h.eps;
-  const float upd = h.step_size * __fdiv_rn(m1, denom);
+  // sqrtf and '/' are IEEE-correct here (hipcc's default
+  // -fhip-fp32-correctly-rounded-divide-sqrt); the __fsqrt_rn intrinsic is not.
+  const float denom = sqrtf(v) / h.sqrt_bc2 + h.eps;
+  const float upd = h.step_size * (m1 / denom);
   return pd - upd;
 }
 

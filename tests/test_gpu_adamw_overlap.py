@@ -1,0 +1,189 @@
+"""GPU parity of the fused AdamW local step and of the two-stream round schedule
+(inner AdamW steps on the main stream, outer update in split form on a side
+stream) against the CPU oracle, plus bit equality of the overlapped schedule with
+the same launches issued serially.  Tolerance: 1e-5 relative per element against
+the fp32-ordered oracle (both sides evaluate the same unfused expression with
+IEEE division and square root, so bit equality is the usual outcome)."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import co2_inputs
+import paper_2401_16265_amd as co2
+from paper_2401_16265_amd.schedule import AdamWConfig, CO2Worker
+from harness import assert_close
+from oracle import co2_oracle
+
+pytestmark = pytest.mark.gpu
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+
+@pytest.fixture()
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    d = torch.device("cuda:0")
+    yield d
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+ADAM_TABLES = {
+    1: [0, 1], 511: [0, 511], 512: [0, 100, 512], 513: [0, 512, 513],
+    4099: [0, 0, 7, 2048, 2048, 4099], 100003: [0, 33333, 66666, 100003],
+}
+
+
+@pytest.mark.parametrize("n", sorted(ADAM_TABLES))
+@pytest.mark.parametrize("inplace", [True, False])
+def test_adamw_parity(dev, n, inplace):
+    table = ADAM_TABLES[n]
+    seg = co2.SegmentTable(table, dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    p = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(1, 1))
+    anchor = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(1, 2))
+    m1, v = torch.zeros(n, **f32), torch.zeros(n, **f32)
+    dout = torch.empty(n, **f32)
+    sq = torch.empty(seg.S, dtype=torch.float64, device=dev)
+    ws = torch.empty(co2.workspace_bytes(n, seg.S, 1), dtype=torch.uint8, device=dev)
+    o_p, o_m1, o_v, o_anchor = p.cpu().numpy(), m1.cpu().numpy(), v.cpu().numpy(), anchor.cpu().numpy()
+    for k in range(1, 5):
+        g = co2_inputs.fill_bf16_normal_(torch.empty(n, dtype=torch.bfloat16, device=dev), 1e-3,
+                                         co2_inputs.seed_for(1, 10, k))
+        with_dout, with_norm = k % 2 == 0, k in (1, 2)
+        p_out = p if inplace else torch.empty_like(p)
+        print(f"  adamw n={n} k={k} inplace={inplace} dout={with_dout} norm={with_norm}", flush=True)
+        co2.co2_inner_adamw(n, p, p_out, g, m1, v, adam_step=k, anchor=anchor if with_dout else None,
+                            delta_out=dout if with_dout else None, table=seg if with_norm else None,
+                            step_sq_out=sq if with_norm else None, workspace=ws if with_norm else None,
+                            **HP)
+        o_out = o_p if inplace else np.empty_like(o_p)
+        out = co2_oracle.adamw_f32(p_in=o_p, p_out=o_out, grad_bf16=bits(g), exp_avg=o_m1,
+                                   exp_avg_sq=o_v, k=k, anchor=o_anchor if with_dout else None,
+                                   seg_off=table, want_step_sq=with_norm, **HP)
+        p, o_p = p_out, o_out
+        assert_close(p.cpu().numpy(), o_p, "params")
+        assert_close(m1.cpu().numpy(), o_m1, "exp_avg")
+        assert_close(v.cpu().numpy(), o_v, "exp_avg_sq")
+        if with_dout:
+            assert_close(dout.cpu().numpy(), out["dout"], "delta_out")
+        if with_norm:
+            assert_close(sq.cpu().numpy(), out["step_sq"], "step_sq", tol=1e-12)
+            fsn = torch.empty(seg.S, **f32)
+            co2.co2_sqrt_to_f32(sq, fsn, seg.S)
+            assert_close(fsn.cpu().numpy(), np.sqrt(out["step_sq"]).astype(np.float32), "sqrt", tol=1e-6)
+
+
+class OracleWorker:
+    """The same round, step by step, through the CPU oracle on sampled segments."""
+
+    def __init__(self, table, sample, K, tau, alpha, beta, phi, c, params_init):
+        self.sample = sample
+        self.full_table = table
+        sizes = [table[s + 1] - table[s] for s in sample]
+        self.table = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        self.K, self.tau, self.alpha, self.beta, self.phi, self.c = K, tau, alpha, beta, phi, c
+        self.params = self.gather(params_init)
+        n = self.params.size
+        self.exp_avg, self.exp_avg_sq = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        self.anchor = self.params.copy()
+        self.momentum = np.zeros(n, np.float32)
+        self.own_prev = np.zeros(n, np.float32)
+        self.fsn_prev = None
+        self.t, self.k = 0, 0
+
+    def gather(self, buf, as_bits=False):
+        parts = [buf[self.full_table[s]:self.full_table[s + 1]] for s in self.sample]
+        t = torch.cat(parts) if len(parts) > 1 else parts[0]
+        return bits(t) if as_bits else t.cpu().numpy().copy()
+
+    def round(self, grads, peers):
+        # inner loop: tau AdamW steps from the anchor
+        fsn = None
+        for k in range(self.tau):
+            self.k += 1
+            first, last = k == 0, k == self.tau - 1
+            out = co2_oracle.adamw_f32(
+                p_in=self.anchor if first else self.params, p_out=self.params,
+                grad_bf16=self.gather(grads[k], as_bits=True), exp_avg=self.exp_avg,
+                exp_avg_sq=self.exp_avg_sq, k=self.k, anchor=self.anchor if last else None,
+                seg_off=self.table, want_step_sq=first, **HP)
+            if first:
+                fsn = np.sqrt(out["step_sq"]).astype(np.float32)
+            if last:
+                own_cur = out["dout"]
+        # outer update of round t from round t-1's pseudo-gradients (split form)
+        d = [self.own_prev] + [self.gather(pb) for pb in peers] if self.t >= 1 else None
+        a_next = np.empty_like(self.anchor)
+        self.lam = co2_oracle.outer_step_f32(
+            seg_off=self.table, alpha=self.alpha, beta=self.beta, phi=self.phi, c=self.c,
+            tau=self.tau, step=self.t, x=None, a=self.anchor, a_out=a_next, m=self.momentum,
+            deltas=d, first_step_norm=self.fsn_prev)["lam"]
+        self.anchor, self.own_prev, self.fsn_prev = a_next, own_cur, fsn
+        self.t += 1
+
+
+def run_rounds(dev, table, sample, K, tau, rounds, seed, phi):
+    seg = co2.SegmentTable(table, dev)
+    n = seg.n
+    f32 = dict(dtype=torch.float32, device=dev)
+    init = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(seed, 1))
+    mk = lambda: CO2Worker(seg, K, tau, 1.0, 0.9, phi, 1.0, AdamWConfig(**HP), dev, init)  # noqa: E731
+    w_ov, w_se = mk(), mk()
+    ow = OracleWorker(table, sample, K, tau, 1.0, 0.9, phi, 1.0, init)
+    grads = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)]
+    for t in range(rounds):
+        print(f"  round {t}: n={n} K={K} tau={tau}", flush=True)
+        for k, g in enumerate(grads):
+            co2_inputs.fill_bf16_normal_(g, 1e-3, co2_inputs.seed_for(seed, 10 + k, t))
+        for j, (pa, pb) in enumerate(zip(w_ov.peers, w_se.peers)):
+            co2_inputs.fill_normal_(pa, 1e-3, co2_inputs.seed_for(seed, 200 + j, t))
+            pb.copy_(pa)
+        w_ov.round_overlapped(grads)
+        w_se.round_serial(grads)
+        ow.round(grads, w_ov.peers)
+        torch.cuda.synchronize()
+        # overlapped == serial, bit for bit
+        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam"):
+            assert torch.equal(getattr(w_ov, name), getattr(w_se, name)), f"{name}: overlap != serial"
+        for i in range(2):
+            assert torch.equal(w_ov.anchor[i], w_se.anchor[i]) and torch.equal(w_ov.own[i], w_se.own[i])
+        # against the oracle (sampled segments)
+        nxt = w_ov.anchor[(t + 1) % 2]
+        assert_close(ow.gather(w_ov.params), ow.params, "params")
+        assert_close(ow.gather(w_ov.exp_avg), ow.exp_avg, "exp_avg")
+        assert_close(ow.gather(w_ov.exp_avg_sq), ow.exp_avg_sq, "exp_avg_sq")
+        assert_close(ow.gather(w_ov.momentum), ow.momentum, "momentum")
+        assert_close(ow.gather(nxt), ow.anchor, "next anchor")
+        assert_close(ow.gather(w_ov.own[t % 2]), ow.own_prev, "pseudo-gradient")
+        if t >= 1:
+            assert_close(w_ov.lam[sample].cpu().numpy(), ow.lam, "Lambda")
+    return w_ov, ow
+
+
+def test_overlapped_rounds_small(dev):
+    table = co2_inputs.gpt_table(layers=2, d=65, ffn=257, vocab=1001, ctx=33)
+    w, ow = run_rounds(dev, table, list(range(len(table) - 1)), K=4, tau=3, rounds=6, seed=4,
+                       phi=1e-3)
+    assert np.all(ow.lam >= 1.0) and np.any(ow.lam > 1.0)
+
+
+def test_overlapped_rounds_tau_one(dev):
+    table = [0, 5, 4096, 10001]
+    run_rounds(dev, table, [0, 1, 2], K=2, tau=1, rounds=4, seed=5, phi=1.0)
+
+
+def test_overlapped_rounds_350m(dev):
+    """The overlapped-round workload at its real size (354.8M params, K=8, tau=4),
+    three rounds; oracle on a sample of whole segments."""
+    cfg = co2_inputs.CONFIGS["350m_overlap"]
+    table = co2_inputs.config_table(cfg)
+    assert table[-1] == 354_823_168
+    S = len(table) - 1
+    sample = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, S - 2, S - 1]
+    run_rounds(dev, table, sample, K=cfg.K, tau=cfg.tau, rounds=3, seed=6, phi=cfg.phi)

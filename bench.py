@@ -41,6 +41,7 @@ def parse():
                     help="carried: steady-state single pass (norm sums carried from the "
                          "previous round's sweep); two_pass: separate norm pass every round")
     ap.add_argument("--workload", default="1p3b")
+    ap.add_argument("--K", type=int, default=0, help="override the workload's worker count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
     return ap.parse_args()
@@ -95,6 +96,61 @@ def cpu_baseline(cfg, table, sample_elems: int, gen_device="cpu"):
                       f"workload, K={cfg.K}, {reps} outer steps in {el:.1f} s, g++ -O2, 1 thread"}
 
 
+def overlap_bench(args):
+    """Overlapped-round workload: tau fused AdamW steps on the main stream while the
+    outer update (split form) runs on a side stream; steady-state round time against
+    the same launches issued serially.  Prints its own JSON line."""
+    import statistics
+
+    import torch
+
+    import co2_inputs
+    import paper_2401_16265_amd as co2
+    from paper_2401_16265_amd.schedule import AdamWConfig, CO2Worker
+
+    dev = torch.device("cuda:0")
+    cfg = co2_inputs.CONFIGS["350m_overlap"]
+    table = co2_inputs.config_table(cfg)
+    seg = co2.SegmentTable(table, dev)
+    n, K, tau = seg.n, cfg.K, cfg.tau
+    hp = {k: v for k, v in cfg.adamw.items() if k != "grad_std"}
+    init = co2_inputs.fill_normal_(torch.empty(n, dtype=torch.float32, device=dev), cfg.param_std,
+                                   co2_inputs.seed_for(cfg.seed, 1))
+    grads = [co2_inputs.fill_bf16_normal_(torch.empty(n, dtype=torch.bfloat16, device=dev),
+                                          cfg.adamw["grad_std"], co2_inputs.seed_for(cfg.seed, 10 + k))
+             for k in range(tau)]
+    rounds = max(args.steps, 12)
+    res = {}
+    for mode in ("serial", "overlapped"):
+        w = CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**hp), dev, init)
+        for j, pb in enumerate(w.peers):
+            co2_inputs.fill_normal_(pb, cfg.drift_scale, co2_inputs.seed_for(cfg.seed, 200 + j))
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(rounds):
+            evs[r].record()
+            (w.round_overlapped if mode == "overlapped" else w.round_serial)(grads)
+        evs[rounds].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per = [evs[r].elapsed_time(evs[r + 1]) for r in range(rounds)]
+        res[mode] = {"median_ms": statistics.median(per[10:]), "min_ms": min(per[10:]),
+                     "wall_ms_per_round": wall * 1e3 / rounds}
+        del w
+        torch.cuda.empty_cache()
+    bytes_round = (26 * tau + 8 + 4) * n + (16 + 4 * K) * n   # AdamW steps (+dout, +anchor read) + split outer update
+    out = {"metric": "overlapped round time (tau AdamW steps + outer update)",
+           "value": res["overlapped"]["median_ms"], "unit": "ms", "n_gpus": 1, "steps": rounds,
+           "warmup": 10, "ms_per_step": res["overlapped"]["median_ms"], "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: n={n}, K={K}, tau={tau}, bf16 grads, fp32 master"},
+           "serial": res["serial"], "overlapped": res["overlapped"],
+           "overlap_speedup": res["serial"]["median_ms"] / res["overlapped"]["median_ms"],
+           "round_gbps_algorithmic": bytes_round / (res["overlapped"]["median_ms"] * 1e-3) / 1e9}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -110,8 +166,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "350m_overlap":
+        return overlap_bench(args)
     dev = torch.device("cuda:0")
     cfg = co2_inputs.CONFIGS[args.workload]
+    if args.K:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, K=args.K)
     table = co2_inputs.config_table(cfg)
     seg = co2.SegmentTable(table, dev)
     n, S, K = seg.n, seg.S, cfg.K

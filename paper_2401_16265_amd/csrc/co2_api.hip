@@ -119,16 +119,15 @@ namespace co2 {
 const Tuning& tuning() {
   static const Tuning t = [] {
     Tuning u{};
-    // Keep about 56-64 KB of loads in flight per compute unit: each wavefront
-    // of the sweep holds 1 KB x (3+K) streams.
+    // Measured optimum of resident wavefronts per compute unit for the sweep at
+    // 1.3B parameters (each wavefront holds 1 KB x (3+K) streams of loads):
+    // 8 for K <= 3, 6 for K <= 6, 5 for K <= 11, 4 beyond.
     for (int k = 1; k <= CO2_MAX_K; ++k) {
-      int w = (60 * 1024 + 512 * (3 + k)) / (1024 * (3 + k));
-      if (w < 4) w = 4;
-      if (w > 16) w = 16;
+      const int w = k <= 3 ? 8 : k <= 6 ? 6 : k <= 11 ? 5 : 4;
       u.sweep_waves_per_cu[k] = env_int("CO2_SWEEP_WAVES", w);
     }
     u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
-    u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 6);
+    u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 10);
     u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 6);
     return u;
   }();

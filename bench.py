@@ -89,7 +89,7 @@ def cpu_baseline(cfg, table, sample_elems: int, gen_device="cpu"):
         co2_oracle.outer_step_f32(x=x, a=a, m=m, deltas=d, step=2 + reps, **kw)
         reps += 1
         el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 8:
+        if el > 12.0 or reps >= 64:
             break
     return {"value": n * reps / el, "unit": "params/s", "cores": 1, "kind": "oracle",
             "sample": f"{len(chosen)} whole segments ({n} of {table[-1]} params) of the same "

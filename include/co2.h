@@ -78,6 +78,9 @@ typedef struct co2_params {
                                  which only the pseudo-gradient is formed (Sec. 3.1) */
   void* ev_sweep_begin;       /* optional hipEvent_t recorded on the stream right before */
   void* ev_sweep_end;         /* / right after the fused sweep kernel (timing only)      */
+  int64_t* clipped_out;       /* optional DEVICE int64[S]: per segment, the number of coordinates
+                                 with |m_t| > phi, i.e. clamped in the outer iterate (0 at
+                                 step 0).  Costs two small extra launches when set.       */
 } co2_params;
 
 /* Bytes of DEVICE workspace the calls below need for these sizes (256-byte
@@ -120,7 +123,7 @@ size_t co2_workspace_bytes(int64_t n, int32_t S, int32_t K);
  * (x_{t,0} - x_{t-1,0} = -alpha*Clip(m_{t-1},phi) by the outer-iterate line one round
  * earlier, which is why the numerator is read from the momentum buffer.)
  * step == 0: delta_out = anchor - params; params = anchor_out = anchor; momentum
- * and the workspace are not touched.
+ * is only read (its clipped sum of squares is left in the workspace for round 1).
  *
  * Buffers must not overlap except anchor_out == anchor.  Errors: CO2_EINVAL for
  * NULL/misaligned/overlapping buffers, n<1, S<1, K outside 1..CO2_MAX_K, a bad

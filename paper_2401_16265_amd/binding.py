@@ -25,6 +25,7 @@ class Co2Params(C.Structure):
         ("alpha", C.c_float), ("beta", C.c_float), ("clip_phi", C.c_float),
         ("penalty_c", C.c_float), ("tau", C.c_int32), ("flags", C.c_uint32),
         ("step", C.c_int64), ("ev_sweep_begin", C.c_void_p), ("ev_sweep_end", C.c_void_p),
+        ("clipped_out", C.c_void_p),
     ]
 
 
@@ -175,12 +176,14 @@ def _check(rc: int, where: str, check: bool) -> int:
 
 def make_params(table: SegmentTable, K: int, alpha: float, beta: float, clip_phi: float,
                 penalty_c: float, tau: int, step: int, flags: int = 0,
-                ev_begin: Optional[HipEvent] = None, ev_end: Optional[HipEvent] = None) -> Co2Params:
+                ev_begin: Optional[HipEvent] = None, ev_end: Optional[HipEvent] = None,
+                clipped_out: Optional[torch.Tensor] = None) -> Co2Params:
     return Co2Params(n=table.n, S=table.S, K=K, seg_off=table.host_ptr, seg_off_dev=table.dev_ptr,
                      alpha=alpha, beta=beta, clip_phi=clip_phi, penalty_c=penalty_c, tau=tau,
                      flags=flags, step=step,
                      ev_sweep_begin=ev_begin.handle if ev_begin else None,
-                     ev_sweep_end=ev_end.handle if ev_end else None)
+                     ev_sweep_end=ev_end.handle if ev_end else None,
+                     clipped_out=_dp(clipped_out, torch.int64))
 
 
 def co2_outer_step(p: Co2Params, params, anchor, anchor_out, momentum, deltas, delta_out,

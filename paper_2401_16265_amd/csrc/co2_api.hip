@@ -42,6 +42,7 @@ inline bool table_ok(int64_t n, int32_t S, const int64_t* seg_off) {
 struct Workspace {
   double* norm_part[2];    // pass-1 partials (kNormTile tiles): clipped momentum, deltas[0]
   double* carry_part[2];   // partials left by the sweep (kSweepTile tiles) for the next round
+  double* clip_part;       // per-slot counts of clamped coordinates left by the sweep
   double* adam_part;       // partials of the AdamW step norm (kAdamTile tiles)
   double* sub[2];          // [S*split] sub-sums of each segment's slots
   double* seg_sq;          // [2][S] per-segment sums
@@ -72,6 +73,7 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
   w.norm_part[1] = reinterpret_cast<double*>(take(sn));
   w.carry_part[0] = reinterpret_cast<double*>(take(ss));
   w.carry_part[1] = reinterpret_cast<double*>(take(ss));
+  w.clip_part = reinterpret_cast<double*>(take(ss));
   w.adam_part = reinterpret_cast<double*>(take(sa));
   w.split = split_of(S);
   const size_t sub = sizeof(double) * static_cast<size_t>(S) * static_cast<size_t>(w.split);
@@ -101,6 +103,13 @@ inline hipError_t enqueue_totals(const Workspace& w, const double* part, int64_t
                                        w.sub[1], st);
   if (e != hipSuccess) return e;
   return co2::launch_totals_finish(w.sub[0], S, w.split, out, st);
+}
+
+inline hipError_t enqueue_counts(const Workspace& w, const co2_params* p, hipStream_t st) {
+  hipError_t e = co2::launch_slot_sums(w.clip_part, nullptr, p->seg_off_dev, p->S, co2::kSweepTile,
+                                       w.split, w.sub[0], w.sub[1], st);
+  if (e != hipSuccess) return e;
+  return co2::launch_counts_finish(w.sub[0], p->S, w.split, p->clipped_out, st);
 }
 
 int env_int(const char* name, int fallback) {
@@ -191,7 +200,8 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
     for (int j = i + 1; j < 5; ++j)
       if (overlaps(vec[i], nb, vec[j], nb)) return CO2_EINVAL;
   }
-  if (!aligned16(p->seg_off_dev) || !aligned16(first_step_norm) || !aligned16(lambda_out))
+  if (!aligned16(p->seg_off_dev) || !aligned16(first_step_norm) || !aligned16(lambda_out) ||
+      !aligned16(p->clipped_out))
     return CO2_EINVAL;
   if (overlaps(first_step_norm, sb, lambda_out, sb)) return CO2_EINVAL;
   co2::DeltaPtrs dptr{};
@@ -218,7 +228,7 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   g.dout = delta_out; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
   g.alpha = p->alpha; g.beta = p->beta; g.phi = p->clip_phi;
   g.rK = static_cast<float>(1.0 / static_cast<double>(p->K));
-  g.part_m = w.carry_part[0]; g.part_d = w.carry_part[1];
+  g.part_m = w.carry_part[0]; g.part_d = w.carry_part[1]; g.part_c = w.clip_part;
   const bool has_x = params != nullptr;
   hipError_t e;
 
@@ -228,6 +238,7 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
     if ((e = co2::launch_first_round(has_x, g, st)) != hipSuccess) return fail_hip(e);
     if (p->ev_sweep_end && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_end), st)) != hipSuccess)
       return fail_hip(e);
+    if (p->clipped_out && (e = enqueue_counts(w, p, st)) != hipSuccess) return fail_hip(e);
     return CO2_OK;
   }
 
@@ -250,6 +261,7 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   if ((e = co2::launch_fused_sweep(p->K, has_x, g, st)) != hipSuccess) return fail_hip(e);
   if (p->ev_sweep_end && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_end), st)) != hipSuccess)
     return fail_hip(e);
+  if (p->clipped_out && (e = enqueue_counts(w, p, st)) != hipSuccess) return fail_hip(e);
   return CO2_OK;
 }
 

@@ -22,6 +22,7 @@ struct SweepArgs {
   float alpha, beta, phi, rK;
   double* part_m;           // per-slot sums of Clip(m',phi)^2 for the next round
   double* part_d;           // per-slot sums of delta_out^2 for the next round
+  double* part_c;           // per-slot counts of |m'| > phi (exact small integers)
 };
 
 struct AdamArgs {
@@ -61,6 +62,7 @@ hipError_t launch_slot_sums(const double* part_a, const double* part_b, const in
                             int S, int64_t tile_elems, int split, double* out_a, double* out_b,
                             hipStream_t st);
 hipError_t launch_totals_finish(const double* sub, int S, int split, double* out, hipStream_t st);
+hipError_t launch_counts_finish(const double* sub, int S, int split, int64_t* out, hipStream_t st);
 hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S, int split,
                                 const float* first_step_norm, float c, float alpha, int tau,
                                 double* seg_sq, float* inv, float* lambda_out, hipStream_t st);

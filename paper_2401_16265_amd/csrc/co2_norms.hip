@@ -140,6 +140,13 @@ __global__ __launch_bounds__(kReduceBlock) void totals_finish(
   if (s < S) out[s] = add_in_order(sub, int64_t(s) * split, split);
 }
 
+// Per-segment counts (exact integers carried as doubles) to int64.
+__global__ __launch_bounds__(kReduceBlock) void counts_finish(
+    const double* __restrict__ sub, int S, int split, int64_t* __restrict__ out) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
+  if (s < S) out[s] = static_cast<int64_t>(add_in_order(sub, int64_t(s) * split, split));
+}
+
 // Lambda_t per segment (Algorithm 1, gap update; Eq. 3), fp64:
 //   numerator   alpha*sqrt(M2),  M2 = sum Clip(m_{t-1},phi)^2
 //   denominator tau*first_step_norm[s], or sqrt(P2), P2 = sum d_0^2
@@ -204,6 +211,13 @@ hipError_t launch_slot_sums(const double* part_a, const double* part_b, const in
 hipError_t launch_totals_finish(const double* sub, int S, int split, double* out,
                                 hipStream_t st) {
   hipLaunchKernelGGL(totals_finish, dim3((S + kReduceBlock - 1) / kReduceBlock),
+                     dim3(kReduceBlock), 0, st, sub, S, split, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_counts_finish(const double* sub, int S, int split, int64_t* out,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(counts_finish, dim3((S + kReduceBlock - 1) / kReduceBlock),
                      dim3(kReduceBlock), 0, st, sub, S, split, out);
   return hipGetLastError();
 }

@@ -54,7 +54,8 @@ template <int K, bool HAS_X>
 __global__ __launch_bounds__(kWave) void fused_sweep(
     float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, float* dout,
     const float* __restrict__ inv_tab, const int64_t* __restrict__ off, int S, int64_t n,
-    SweepScalars h, double* __restrict__ part_m, double* __restrict__ part_d) {
+    SweepScalars h, double* __restrict__ part_m, double* __restrict__ part_d,
+    double* __restrict__ part_c) {
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int lane = threadIdx.x;
@@ -76,6 +77,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     const float inv = inv_tab[s_lo];
     float mc[4], xc[4], dc[4];
     double acc_m = 0.0, acc_d = 0.0;
+    int nclip = 0;                                  // wavefront-uniform
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float ae = comp(va, e);
@@ -89,6 +91,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
       mc[e] = comp(vm, e);
       xc[e] = outer_coord(ae, mc[e], mean_of_workers<K>(dk, h.rK), inv, h);
       acc_m += sq(clip_coord(mc[e], h.phi));
+      nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));
     }
     const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
     if (HAS_X) {
@@ -103,6 +106,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     if (lane == 0) {
       part_m[tile + s_lo] = tm;
       if (HAS_X) part_d[tile + s_lo] = td;
+      part_c[tile + s_lo] = static_cast<double>(nclip);
     }
     return;
   }
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     const int64_t hi = off[s + 1] < end ? off[s + 1] : end;
     if (lo >= hi) continue;
     const float inv = inv_tab[s];
-    double acc_m = 0.0, acc_d = 0.0;
+    double acc_m = 0.0, acc_d = 0.0, acc_c = 0.0;
     for (int64_t j = lo + lane; j < hi; j += kWave) {
       const float a = a_in[j];
       float mj = m[j];
@@ -126,6 +130,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
       if (HAS_X) dj = a - x[j];
       const float xn = outer_coord(a, mj, mean_of_workers<K>(dk, h.rK), inv, h);
       acc_m += sq(clip_coord(mj, h.phi));
+      if (fabsf(mj) > h.phi) acc_c += 1.0;
       if (HAS_X) {
         acc_d += sq(dj);
         dout[j] = dj;
@@ -135,11 +140,13 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
       a_out[j] = xn;
     }
     const double tm = wave_sum(acc_m);
+    const double tc = wave_sum(acc_c);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
     if (lane == 0) {
       part_m[tile + s] = tm;
       if (HAS_X) part_d[tile + s] = td;
+      part_c[tile + s] = tc;
     }
   }
 }
@@ -152,7 +159,7 @@ template <bool HAS_X>
 __global__ __launch_bounds__(kWave) void first_round(
     float* x, const float* a_in, float* a_out, const float* __restrict__ m, float* dout,
     const int64_t* __restrict__ off, int S, int64_t n, float phi,
-    double* __restrict__ part_m, double* __restrict__ part_d) {
+    double* __restrict__ part_m, double* __restrict__ part_d, double* __restrict__ part_c) {
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
@@ -181,6 +188,7 @@ __global__ __launch_bounds__(kWave) void first_round(
     if (lane == 0) {
       part_m[tile + s] = tm;
       if (HAS_X) part_d[tile + s] = td;
+      part_c[tile + s] = 0.0;                       // no outer iterate in the first round
     }
   }
 }
@@ -211,11 +219,11 @@ static hipError_t launch_sweep_k(bool has_x, const SweepArgs& g, hipStream_t st)
   if (has_x) {
     hipLaunchKernelGGL((fused_sweep<K, true>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
                        g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.part_m,
-                       g.part_d);
+                       g.part_d, g.part_c);
   } else {
     hipLaunchKernelGGL((fused_sweep<K, false>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
                        g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.part_m,
-                       g.part_d);
+                       g.part_d, g.part_c);
   }
   return hipGetLastError();
 }
@@ -235,10 +243,10 @@ hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
   if (has_x) {
     hipLaunchKernelGGL(first_round<true>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in, g.a_out,
-                       g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d);
+                       g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d, g.part_c);
   } else {
     hipLaunchKernelGGL(first_round<false>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in,
-                       g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d);
+                       g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d, g.part_c);
   }
   return hipGetLastError();
 }

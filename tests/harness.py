@@ -70,6 +70,7 @@ class OuterStepHarness:
         self.own = [torch.zeros(n, **f32), torch.zeros(n, **f32)]   # ping-pong: delta_out / deltas[0]
         self.peers = [torch.zeros(n, **f32) for _ in range(K - 1)]
         self.lam = torch.empty(self.S, **f32)
+        self.clipped = torch.full((self.S,), -1, dtype=torch.int64, device=device)
         self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
         self.fsn = None
         if use_first_step_norm:
@@ -133,7 +134,7 @@ class OuterStepHarness:
         # ---- device
         ev_b, ev_e = events if events else (None, None)
         p = co2.make_params(self.seg, hp.K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
-                            ev_b, ev_e)
+                            ev_b, ev_e, self.clipped)
         deltas = [cur] + self.peers
         a_out = self.a
         if split:
@@ -189,6 +190,13 @@ class OuterStepHarness:
         res["delta_out"] = assert_close(g_d, self.o_own, "delta_out")
         res["bit_exact"] = bool(np.array_equal(g_x, self.o_x) and np.array_equal(g_m, self.o_m)
                                 and np.array_equal(g_d, self.o_own) and np.array_equal(g_a, self.o_a))
+        # per-segment count of clamped coordinates (integers: exact)
+        flag = np.abs(self.o_m) > np.float32(self.hp.phi) if self.last_step >= 1 else np.zeros(self.o_m.size, bool)
+        csum = np.concatenate([[0], np.cumsum(flag)])
+        want_c = csum[self.otable[1:]] - csum[self.otable[:-1]]
+        got_c = self.clipped[self.sample].cpu().numpy()
+        assert np.array_equal(got_c, want_c), "clipped-coordinate counts differ"
+        assert int(want_c.sum()) == self.last["nclipped"]
         if self.last_step >= 1:
             g_lam = self.lam[self.sample].cpu().numpy()
             res["lambda"] = assert_close(g_lam, self.last["lam"], "Lambda")

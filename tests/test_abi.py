@@ -37,7 +37,7 @@ def test_params_struct_layout_matches_header():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"([A-Za-z_][A-Za-z0-9_]*)\s*;", body)
     assert fields == [f[0] for f in co2.Co2Params._fields_]
-    assert C.sizeof(co2.Co2Params) == 8 + 4 + 4 + 8 + 8 + 16 + 4 + 4 + 8 + 8 + 8
+    assert C.sizeof(co2.Co2Params) == 8 + 4 + 4 + 8 + 8 + 16 + 4 + 4 + 8 + 8 + 8 + 8
 
 
 def test_strerror_and_workspace_bytes():
@@ -49,8 +49,8 @@ def test_strerror_and_workspace_bytes():
     w1 = co2.workspace_bytes(1 << 20, 8, 4)
     w2 = co2.workspace_bytes(1 << 24, 8, 4)
     assert 0 < w1 < w2 and w1 % 256 == 0
-    # bounded: under a tenth of a byte per element
-    assert co2.workspace_bytes(1343868928, 292, 8) < 1343868928 // 10
+    # bounded: about an eighth of a byte per element
+    assert co2.workspace_bytes(1343868928, 292, 8) < 1343868928 // 7
 
 
 A = 0x7F0000000000          # fake, 256-byte aligned "device" addresses: never dereferenced
@@ -144,3 +144,26 @@ def test_norms_and_adamw_reject_bad_arguments():
     assert adam(sq=_fake(5), seg=keep.ctypes.data, segd=_fake(20), S=2, ws=_fake(8), wsb=16) == co2.CO2_EWORKSPACE
     assert L.co2_sqrt_to_f32(None, _fake(1), 4, None) == co2.CO2_EINVAL
     assert L.co2_copy_f32(_fake(0), _fake(0), 16, None) == co2.CO2_EINVAL
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path, monkeypatch):
+    """No CPU fallback: if libco2.so is absent and cannot be built, loading raises."""
+    import subprocess
+
+    from paper_2401_16265_amd import binding, build
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "libco2.so"))
+    monkeypatch.setenv("HIPCC", "/bin/false")
+    with pytest.raises((subprocess.CalledProcessError, OSError)):
+        binding.lib()
+    monkeypatch.undo()
+    assert binding.lib() is not None
+
+
+def test_package_does_not_import_the_oracle():
+    import subprocess
+    import sys
+    code = ("import sys; import paper_2401_16265_amd, paper_2401_16265_amd.schedule; "
+            "bad=[m for m in sys.modules if m.startswith('oracle')]; sys.exit(1 if bad else 0)")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    assert subprocess.run([sys.executable, "-c", code], cwd=root).returncode == 0

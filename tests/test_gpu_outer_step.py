@@ -141,6 +141,74 @@ def test_carried_norms_equal_two_pass(dev):
         assert torch.equal(hs[0].m, hs[1].m) and torch.equal(hs[0].a, hs[1].a)
 
 
+def test_resume_from_saved_state(dev):
+    """Checkpoint/resume: the state that defines a round is anchor, momentum, the
+    in-flight pseudo-gradients and the round index.  Restoring it into fresh
+    buffers (fresh workspace, so one two-pass round before carried sums exist
+    again) continues bit for bit like the uninterrupted run."""
+    table = co2_inputs.gpt_table(layers=2, d=97, ffn=385, vocab=2001, ctx=31)
+    mk = lambda: OuterStepHarness(table, HP(K=4, phi=2e-3, beta=0.95), dev, seed=9, momentum_std=0.0)  # noqa: E731
+    ref, run = mk(), mk()
+    for t in range(6):
+        ref.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+    for t in range(3):
+        run.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+    saved = dict(a=run.a.clone(), m=run.m.clone(), x=run.x.clone(),
+                 own=[o.clone() for o in run.own], t=run.t)
+    # "restart": overwrite every live buffer, then restore from the checkpoint
+    for b in [run.a, run.m, run.x, run.ws] + run.own + run.peers:
+        b.fill_(0) if b.dtype != torch.uint8 else b.fill_(255)
+    run.a.copy_(saved["a"]); run.m.copy_(saved["m"]); run.x.copy_(saved["x"])
+    for o, so in zip(run.own, saved["own"]):
+        o.copy_(so)
+    for t in range(3, 6):
+        run.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 4 else 0)
+    for name in ("a", "m", "x", "lam"):
+        assert torch.equal(getattr(ref, name), getattr(run, name)), name
+
+
+def test_outer_step_in_a_hip_graph(dev):
+    """The call only enqueues kernels, so a caller may capture it in a HIP graph
+    (no memset nodes are recorded).  Replays are compared with eager calls."""
+    table = co2_inputs.gpt_table(layers=2, d=64, ffn=256, vocab=1001, ctx=32)
+    seg = co2.SegmentTable(table, dev)
+    n, S, K = seg.n, seg.S, 4
+    g = torch.Generator(device=dev); g.manual_seed(3)
+    rnd = lambda std: torch.randn(n, device=dev, generator=g) * std  # noqa: E731
+    a0, m0 = rnd(0.02), rnd(0.01)
+    deltas = [rnd(1e-3) for _ in range(K)]
+    noise = [rnd(1e-3) for _ in range(4)]
+
+    def fresh():
+        return dict(a=a0.clone(), m=m0.clone(), x=a0.clone(), dout=torch.empty(n, device=dev),
+                    lam=torch.empty(S, device=dev),
+                    ws=torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev))
+
+    def call(st, step):
+        p = co2.make_params(seg, K, 1.0, 0.9, 2e-3, 1.0, 4, step)
+        co2.co2_outer_step(p, st["x"], st["a"], st["a"], st["m"], deltas, st["dout"], None,
+                           st["lam"], st["ws"])
+
+    eager, graphed = fresh(), fresh()
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(graphed, 1)                                   # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    graphed = fresh()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(graphed, 1)
+    graphed["a"].copy_(a0); graphed["m"].copy_(m0)          # capture does not execute
+    for r in range(4):
+        eager["x"].copy_(eager["a"] + noise[r]); graphed["x"].copy_(graphed["a"] + noise[r])
+        call(eager, 1)
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("a", "m", "x", "dout", "lam"):
+            assert torch.equal(eager[name], graphed[name]), f"replay {r}: {name}"
+
+
 # ------------------------------------------------------------------ norms entry point
 def test_pseudo_grad_norms(dev, oracle):
     table = [0, 0, 13, 2049, 8192, 8193, 70001]

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kWave) void adamw_step(
     int64_t n, const float* p_in, float* p_out, const uint16_t* __restrict__ grad,
     float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq, AdamScalars h,
     const float* __restrict__ anchor, float* __restrict__ dout,
-    const int64_t* __restrict__ off, int S, double* __restrict__ part) {
+    const int64_t* __restrict__ off, int S, SlotRec* __restrict__ slots) {
   constexpr int U = kAdamU;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kAdamTile;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kWave) void adamw_step(
     }
     if (HAS_NORM) {
       const double t = wave_sum(acc);
-      if (lane == 0) part[tile + s_lo] = t;
+      write_slot(slots, tile + s_lo, lane, t, 0.0, 0.0);
     }
     return;
   }
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kWave) void adamw_step(
     }
     if (HAS_NORM) {
       const double t = wave_sum(acc);
-      if (lane == 0) part[tile + s] = t;
+      write_slot(slots, tile + s, lane, t, 0.0, 0.0);
     }
   }
 }
@@ -134,11 +134,11 @@ hipError_t launch_adamw(const AdamArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kAdamTile - 1) / kAdamTile);
   const unsigned lds = throttle_lds_bytes(tuning().adam_waves_per_cu);
   const AdamScalars h{g.beta1, g.beta2, g.omb1, g.omb2, g.decay, g.step_size, g.sqrt_bc2, g.eps};
-  const bool has_dout = g.dout != nullptr, has_norm = g.part != nullptr;
+  const bool has_dout = g.dout != nullptr, has_norm = g.slots != nullptr;
 #define CO2_ADAM_LAUNCH(D, N)                                                              \
   hipLaunchKernelGGL((adamw_step<D, N>), dim3(tiles), dim3(kWave), lds, st, g.n, g.p_in,   \
                      g.p_out, g.grad, g.exp_avg, g.exp_avg_sq, h, g.anchor, g.dout,        \
-                     g.off_dev, g.S, g.part)
+                     g.off_dev, g.S, g.slots)
   if (has_dout && has_norm) CO2_ADAM_LAUNCH(true, true);
   else if (has_dout) CO2_ADAM_LAUNCH(true, false);
   else if (has_norm) CO2_ADAM_LAUNCH(false, true);

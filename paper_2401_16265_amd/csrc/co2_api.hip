@@ -37,13 +37,12 @@ inline bool table_ok(int64_t n, int32_t S, const int64_t* seg_off) {
   return true;
 }
 
-// Workspace regions (all 256-byte aligned).  Slot arrays hold one fp64 partial
+// Workspace regions (all 256-byte aligned).  Slot arrays hold one 32-byte record
 // per (tile, segment) pair, indexed tile + segment.
 struct Workspace {
-  double* norm_part[2];    // pass-1 partials (kNormTile tiles): clipped momentum, deltas[0]
-  double* carry_part[2];   // partials left by the sweep (kSweepTile tiles) for the next round
-  double* clip_part;       // per-slot counts of clamped coordinates left by the sweep
-  double* adam_part;       // partials of the AdamW step norm (kAdamTile tiles)
+  co2::SlotRec* slots;     // records of the norm pass (kNormTile tiles), consumed by stage 2,
+                           // then of the sweep (kSweepTile tiles), kept for the next round
+  co2::SlotRec* adam_slots;  // records of the AdamW step norm (kAdamTile tiles)
   double* sub[2];          // [S*split] sub-sums of each segment's slots
   double* seg_sq;          // [2][S] per-segment sums
   float* inv;              // [S] 1/Lambda
@@ -66,15 +65,11 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
     o += round256(bytes);
     return r;
   };
-  const size_t sn = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kNormTile, S));
-  const size_t ss = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kSweepTile, S));
-  const size_t sa = sizeof(double) * static_cast<size_t>(slots_of(n, co2::kAdamTile, S));
-  w.norm_part[0] = reinterpret_cast<double*>(take(sn));
-  w.norm_part[1] = reinterpret_cast<double*>(take(sn));
-  w.carry_part[0] = reinterpret_cast<double*>(take(ss));
-  w.carry_part[1] = reinterpret_cast<double*>(take(ss));
-  w.clip_part = reinterpret_cast<double*>(take(ss));
-  w.adam_part = reinterpret_cast<double*>(take(sa));
+  static_assert(co2::kSweepTile <= co2::kNormTile, "the sweep's slot region also serves the norm pass");
+  const size_t ss = sizeof(co2::SlotRec) * static_cast<size_t>(slots_of(n, co2::kSweepTile, S));
+  const size_t sa = sizeof(co2::SlotRec) * static_cast<size_t>(slots_of(n, co2::kAdamTile, S));
+  w.slots = reinterpret_cast<co2::SlotRec*>(take(ss));
+  w.adam_slots = reinterpret_cast<co2::SlotRec*>(take(sa));
   w.split = split_of(S);
   const size_t sub = sizeof(double) * static_cast<size_t>(S) * static_cast<size_t>(w.split);
   w.sub[0] = reinterpret_cast<double*>(take(sub));
@@ -86,27 +81,28 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
 }
 
 // Stage 2 of the gap: slots -> per-segment sub-sums -> Lambda, 1/Lambda.
-inline hipError_t enqueue_lambda(const Workspace& w, double* const part[2], int64_t tile_elems,
-                                 const co2_params* p, const float* first_step_norm,
-                                 float* lambda_out, hipStream_t st) {
+inline hipError_t enqueue_lambda(const Workspace& w, int64_t tile_elems, const co2_params* p,
+                                 const float* first_step_norm, float* lambda_out,
+                                 hipStream_t st) {
   const bool need_d0 = first_step_norm == nullptr;
-  hipError_t e = co2::launch_slot_sums(part[0], need_d0 ? part[1] : nullptr, p->seg_off_dev, p->S,
-                                       tile_elems, w.split, w.sub[0], w.sub[1], st);
+  hipError_t e = co2::launch_slot_sums(w.slots, 0, need_d0, p->seg_off_dev, p->S, tile_elems,
+                                       w.split, w.sub[0], w.sub[1], st);
   if (e != hipSuccess) return e;
   return co2::launch_lambda_finish(w.sub[0], w.sub[1], p->S, w.split, first_step_norm,
                                    p->penalty_c, p->alpha, p->tau, w.seg_sq, w.inv, lambda_out, st);
 }
 
-inline hipError_t enqueue_totals(const Workspace& w, const double* part, int64_t tile_elems,
-                                 const int64_t* off_dev, int32_t S, double* out, hipStream_t st) {
-  hipError_t e = co2::launch_slot_sums(part, nullptr, off_dev, S, tile_elems, w.split, w.sub[0],
-                                       w.sub[1], st);
+inline hipError_t enqueue_totals(const Workspace& w, const co2::SlotRec* slots, int col,
+                                 int64_t tile_elems, const int64_t* off_dev, int32_t S,
+                                 double* out, hipStream_t st) {
+  hipError_t e = co2::launch_slot_sums(slots, col, false, off_dev, S, tile_elems, w.split,
+                                       w.sub[0], w.sub[1], st);
   if (e != hipSuccess) return e;
   return co2::launch_totals_finish(w.sub[0], S, w.split, out, st);
 }
 
 inline hipError_t enqueue_counts(const Workspace& w, const co2_params* p, hipStream_t st) {
-  hipError_t e = co2::launch_slot_sums(w.clip_part, nullptr, p->seg_off_dev, p->S, co2::kSweepTile,
+  hipError_t e = co2::launch_slot_sums(w.slots, 2, false, p->seg_off_dev, p->S, co2::kSweepTile,
                                        w.split, w.sub[0], w.sub[1], st);
   if (e != hipSuccess) return e;
   return co2::launch_counts_finish(w.sub[0], p->S, w.split, p->clipped_out, st);
@@ -228,7 +224,7 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   g.dout = delta_out; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
   g.alpha = p->alpha; g.beta = p->beta; g.phi = p->clip_phi;
   g.rK = static_cast<float>(1.0 / static_cast<double>(p->K));
-  g.part_m = w.carry_part[0]; g.part_d = w.carry_part[1]; g.part_c = w.clip_part;
+  g.slots = w.slots;
   const bool has_x = params != nullptr;
   hipError_t e;
 
@@ -245,13 +241,13 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   // ---- the two sums of squares of Eq. 3, then Lambda per segment
   const bool need_d0 = first_step_norm == nullptr;
   if (carried) {
-    e = enqueue_lambda(w, w.carry_part, co2::kSweepTile, p, first_step_norm, lambda_out, st);
+    e = enqueue_lambda(w, co2::kSweepTile, p, first_step_norm, lambda_out, st);
   } else {
     e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, p->clip_phi,
                                     need_d0 ? dptr.p[0] : nullptr, 0.0f, p->seg_off_dev, p->S,
-                                    p->n, w.norm_part[0], w.norm_part[1], st);
+                                    p->n, w.slots, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = enqueue_lambda(w, w.norm_part, co2::kNormTile, p, first_step_norm, lambda_out, st);
+    e = enqueue_lambda(w, co2::kNormTile, p, first_step_norm, lambda_out, st);
   }
   if (e != hipSuccess) return fail_hip(e);
 
@@ -297,13 +293,13 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
     const float* b1 = pair ? (r + 1 < nbuf ? bufs[r + 1] : momentum) : nullptr;
     const float phi1 = pair ? (r + 1 < nbuf ? 0.0f : p->clip_phi) : 0.0f;
     hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, p->seg_off_dev,
-                                               p->S, p->n, w.norm_part[0], w.norm_part[1], st);
+                                               p->S, p->n, w.slots, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = enqueue_totals(w, w.norm_part[0], co2::kNormTile, p->seg_off_dev, p->S,
+    e = enqueue_totals(w, w.slots, 0, co2::kNormTile, p->seg_off_dev, p->S,
                        sqnorm_out + static_cast<size_t>(r) * p->S, st);
     if (e != hipSuccess) return fail_hip(e);
     if (pair) {
-      e = enqueue_totals(w, w.norm_part[1], co2::kNormTile, p->seg_off_dev, p->S,
+      e = enqueue_totals(w, w.slots, 1, co2::kNormTile, p->seg_off_dev, p->S,
                          sqnorm_out + static_cast<size_t>(r + 1) * p->S, st);
       if (e != hipSuccess) return fail_hip(e);
     }
@@ -365,13 +361,13 @@ int co2_inner_adamw(int64_t n, const float* p_in, float* p_out, const uint16_t* 
   g.sqrt_bc2 = static_cast<float>(std::sqrt(bc2));
   g.eps = eps;
   g.anchor = anchor; g.dout = delta_out;
-  g.off_dev = seg_off_dev; g.S = S; g.part = want_norm ? w.adam_part : nullptr;
+  g.off_dev = seg_off_dev; g.S = S; g.slots = want_norm ? w.adam_slots : nullptr;
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = co2::launch_adamw(g, st);
   if (e != hipSuccess) return fail_hip(e);
   if (want_norm) {
-    e = enqueue_totals(w, w.adam_part, co2::kAdamTile, seg_off_dev, S, step_sq_out, st);
+    e = enqueue_totals(w, w.adam_slots, 0, co2::kAdamTile, seg_off_dev, S, step_sq_out, st);
     if (e != hipSuccess) return fail_hip(e);
   }
   return CO2_OK;

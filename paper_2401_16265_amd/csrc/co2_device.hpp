@@ -31,6 +31,14 @@ constexpr int kReduceBlock = 256;                  // threads of the small reduc
 constexpr int kReduceWaves = kReduceBlock / kWave;
 constexpr int kSegSplit = 32;                      // workgroups that share one segment's slots
 
+// One 32-byte record per (tile, segment) slot, written with a single coalesced
+// 32-byte store (8-byte partial stores cost a full 32-byte HBM write each).
+//   v[0] sum of Clip(m,phi)^2 (or the only quantity of a one-column producer)
+//   v[1] sum of d^2            v[2] count of clamped coordinates      v[3] unused
+struct alignas(32) SlotRec {
+  double v[4];
+};
+
 struct DeltaPtrs {
   const float* p[CO2_MAX_K];
 };
@@ -79,6 +87,15 @@ __device__ __forceinline__ double wave_sum(double v) {
   const double r0 = read_lane(v, 0), r1 = read_lane(v, 16);
   const double r2 = read_lane(v, 32), r3 = read_lane(v, 48);
   return ((r0 + r1) + r2) + r3;
+}
+
+// Lanes 0..3 of the wavefront write one slot record; v0..v2 are wavefront-uniform.
+__device__ __forceinline__ void write_slot(SlotRec* __restrict__ rec, int64_t slot, int lane,
+                                           double v0, double v1, double v2) {
+  if (lane < 4) {
+    const double v = lane == 0 ? v0 : lane == 1 ? v1 : lane == 2 ? v2 : 0.0;
+    reinterpret_cast<double*>(rec + slot)[lane] = v;
+  }
 }
 
 // Sum over a kReduceBlock-thread workgroup (the small reduction kernels only);

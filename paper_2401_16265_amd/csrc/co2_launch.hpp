@@ -20,9 +20,8 @@ struct SweepArgs {
   int S;
   int64_t n;
   float alpha, beta, phi, rK;
-  double* part_m;           // per-slot sums of Clip(m',phi)^2 for the next round
-  double* part_d;           // per-slot sums of delta_out^2 for the next round
-  double* part_c;           // per-slot counts of |m'| > phi (exact small integers)
+  SlotRec* slots;           // per-slot sums of Clip(m',phi)^2 and delta_out^2 for the next
+                            // round's gap, and the count of |m'| > phi
 };
 
 struct AdamArgs {
@@ -37,7 +36,7 @@ struct AdamArgs {
   float* dout;              // nullable
   const int64_t* off_dev;   // nullable (with part)
   int S;
-  double* part;             // per-slot sums of (p' - p_in)^2, nullable
+  SlotRec* slots;           // per-slot sums of (p' - p_in)^2 in column 0, nullable
 };
 
 // Resident wavefronts per compute unit each streaming kernel is capped to
@@ -57,8 +56,10 @@ unsigned throttle_lds_bytes(int waves_per_cu);
 
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
                                   float phi1, const int64_t* off_dev, int S, int64_t n,
-                                  double* part0, double* part1, hipStream_t st);
-hipError_t launch_slot_sums(const double* part_a, const double* part_b, const int64_t* off_dev,
+                                  SlotRec* slots, hipStream_t st);
+// Sums column `col` (and col+1 if two) of each segment's slot records into
+// out_a (and out_b), `split` sub-sums per segment.
+hipError_t launch_slot_sums(const SlotRec* slots, int col, bool two, const int64_t* off_dev,
                             int S, int64_t tile_elems, int split, double* out_a, double* out_b,
                             hipStream_t st);
 hipError_t launch_totals_finish(const double* sub, int S, int split, double* out, hipStream_t st);

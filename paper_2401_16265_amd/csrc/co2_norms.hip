@@ -31,8 +31,7 @@ __device__ __forceinline__ void acc4(double& acc, float4 q, float phi) {
 template <int NB>
 __global__ __launch_bounds__(kWave) void sqnorm_partials(
     const float* __restrict__ b0, float phi0, const float* __restrict__ b1, float phi1,
-    const int64_t* __restrict__ off, int S, int64_t n,
-    double* __restrict__ part0, double* __restrict__ part1) {
+    const int64_t* __restrict__ off, int S, int64_t n, SlotRec* __restrict__ slots) {
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kNormTile;
   const int lane = threadIdx.x;
@@ -61,10 +60,7 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
     const double t0 = wave_sum(a0);
     double t1 = 0.0;
     if (NB == 2) t1 = wave_sum(a1);
-    if (lane == 0) {
-      part0[tile + s_lo] = t0;
-      if (NB == 2) part1[tile + s_lo] = t1;
-    }
+    write_slot(slots, tile + s_lo, lane, t0, t1, 0.0);
     return;
   }
 
@@ -89,17 +85,14 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
     const double t0 = wave_sum(a0);
     double t1 = 0.0;
     if (NB == 2) t1 = wave_sum(a1);
-    if (lane == 0) {
-      part0[tile + s] = t0;
-      if (NB == 2) part1[tile + s] = t1;
-    }
+    write_slot(slots, tile + s, lane, t0, t1, 0.0);
   }
 }
 
 // Sub-sum g of `split` over segment s's slots (tiles t0..t1 of the producing
 // kernel), in a fixed order.  grid = (segments, split); out[q][s*split + g].
 __global__ __launch_bounds__(kReduceBlock) void slot_sums(
-    const double* __restrict__ part_a, const double* __restrict__ part_b,
+    const SlotRec* __restrict__ slots, int col, bool two,
     const int64_t* __restrict__ off, int S, int64_t tile_elems, int split,
     double* __restrict__ out_a, double* __restrict__ out_b) {
   __shared__ double lds[2][kReduceWaves];
@@ -113,16 +106,16 @@ __global__ __launch_bounds__(kReduceBlock) void slot_sums(
       const int64_t c0 = t0 + g * chunk;
       const int64_t c1 = (c0 + chunk - 1 < t1) ? c0 + chunk - 1 : t1;
       for (int64_t t = c0 + threadIdx.x; t <= c1; t += kReduceBlock) {
-        a += part_a[t + s];
-        if (part_b) b += part_b[t + s];
+        a += slots[t + s].v[col];
+        if (two) b += slots[t + s].v[col + 1];
       }
     }
     const double ta = block_sum(a, lds[0]);
     double tb = 0.0;
-    if (part_b) tb = block_sum(b, lds[1]);
+    if (two) tb = block_sum(b, lds[1]);
     if (threadIdx.x == 0) {
       out_a[int64_t(s) * split + g] = ta;
-      if (part_b) out_b[int64_t(s) * split + g] = tb;
+      if (two) out_b[int64_t(s) * split + g] = tb;
     }
   }
 }
@@ -186,24 +179,24 @@ __global__ __launch_bounds__(kReduceBlock) void sqrt_to_f32(const double* __rest
 
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
                                   float phi1, const int64_t* off_dev, int S, int64_t n,
-                                  double* part0, double* part1, hipStream_t st) {
+                                  SlotRec* slots, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>((n + kNormTile - 1) / kNormTile)), block(kWave);
   const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu);
   if (nb == 2) {
     hipLaunchKernelGGL(sqnorm_partials<2>, grid, block, lds, st, b0, phi0, b1, phi1, off_dev, S,
-                       n, part0, part1);
+                       n, slots);
   } else {
     hipLaunchKernelGGL(sqnorm_partials<1>, grid, block, lds, st, b0, phi0, b0, 0.0f, off_dev, S,
-                       n, part0, part0);
+                       n, slots);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_slot_sums(const double* part_a, const double* part_b, const int64_t* off_dev,
+hipError_t launch_slot_sums(const SlotRec* slots, int col, bool two, const int64_t* off_dev,
                             int S, int64_t tile_elems, int split, double* out_a, double* out_b,
                             hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(S < 32768 ? S : 32768), static_cast<unsigned>(split));
-  hipLaunchKernelGGL(slot_sums, grid, dim3(kReduceBlock), 0, st, part_a, part_b, off_dev, S,
+  hipLaunchKernelGGL(slot_sums, grid, dim3(kReduceBlock), 0, st, slots, col, two, off_dev, S,
                      tile_elems, split, out_a, out_b);
   return hipGetLastError();
 }

@@ -54,8 +54,7 @@ template <int K, bool HAS_X>
 __global__ __launch_bounds__(kWave) void fused_sweep(
     float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, float* dout,
     const float* __restrict__ inv_tab, const int64_t* __restrict__ off, int S, int64_t n,
-    SweepScalars h, double* __restrict__ part_m, double* __restrict__ part_d,
-    double* __restrict__ part_c) {
+    SweepScalars h, SlotRec* __restrict__ slots) {
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int lane = threadIdx.x;
@@ -103,11 +102,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
-    if (lane == 0) {
-      part_m[tile + s_lo] = tm;
-      if (HAS_X) part_d[tile + s_lo] = td;
-      part_c[tile + s_lo] = static_cast<double>(nclip);
-    }
+    write_slot(slots, tile + s_lo, lane, tm, td, static_cast<double>(nclip));
     return;
   }
 
@@ -143,11 +138,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     const double tc = wave_sum(acc_c);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
-    if (lane == 0) {
-      part_m[tile + s] = tm;
-      if (HAS_X) part_d[tile + s] = td;
-      part_c[tile + s] = tc;
-    }
+    write_slot(slots, tile + s, lane, tm, td, tc);
   }
 }
 
@@ -158,8 +149,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
 template <bool HAS_X>
 __global__ __launch_bounds__(kWave) void first_round(
     float* x, const float* a_in, float* a_out, const float* __restrict__ m, float* dout,
-    const int64_t* __restrict__ off, int S, int64_t n, float phi,
-    double* __restrict__ part_m, double* __restrict__ part_d, double* __restrict__ part_c) {
+    const int64_t* __restrict__ off, int S, int64_t n, float phi, SlotRec* __restrict__ slots) {
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
@@ -185,11 +175,7 @@ __global__ __launch_bounds__(kWave) void first_round(
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
-    if (lane == 0) {
-      part_m[tile + s] = tm;
-      if (HAS_X) part_d[tile + s] = td;
-      part_c[tile + s] = 0.0;                       // no outer iterate in the first round
-    }
+    write_slot(slots, tile + s, lane, tm, td, 0.0);   // no outer iterate in the first round
   }
 }
 
@@ -218,12 +204,10 @@ static hipError_t launch_sweep_k(bool has_x, const SweepArgs& g, hipStream_t st)
   const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
   if (has_x) {
     hipLaunchKernelGGL((fused_sweep<K, true>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
-                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.part_m,
-                       g.part_d, g.part_c);
+                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
   } else {
     hipLaunchKernelGGL((fused_sweep<K, false>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
-                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.part_m,
-                       g.part_d, g.part_c);
+                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
   }
   return hipGetLastError();
 }
@@ -243,10 +227,10 @@ hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
   if (has_x) {
     hipLaunchKernelGGL(first_round<true>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in, g.a_out,
-                       g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d, g.part_c);
+                       g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
   } else {
     hipLaunchKernelGGL(first_round<false>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in,
-                       g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.part_m, g.part_d, g.part_c);
+                       g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
   }
   return hipGetLastError();
 }

@@ -65,8 +65,9 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
     o += round256(bytes);
     return r;
   };
-  static_assert(co2::kSweepTile <= co2::kNormTile, "the sweep's slot region also serves the norm pass");
-  const size_t ss = sizeof(co2::SlotRec) * static_cast<size_t>(slots_of(n, co2::kSweepTile, S));
+  // one region serves the norm pass and then the sweep: sized for the smaller tile
+  constexpr int64_t kMinTile = co2::kSweepTile < co2::kNormTile ? co2::kSweepTile : co2::kNormTile;
+  const size_t ss = sizeof(co2::SlotRec) * static_cast<size_t>(slots_of(n, kMinTile, S));
   const size_t sa = sizeof(co2::SlotRec) * static_cast<size_t>(slots_of(n, co2::kAdamTile, S));
   w.slots = reinterpret_cast<co2::SlotRec*>(take(ss));
   w.adam_slots = reinterpret_cast<co2::SlotRec*>(take(sa));
@@ -113,7 +114,7 @@ int env_int(const char* name, int fallback) {
   if (!v || !*v) return fallback;
   char* endp = nullptr;
   const long x = std::strtol(v, &endp, 10);
-  if (endp == v || x < 0 || x > 64) return fallback;
+  if (endp == v || x < 0 || x > 64) return fallback;   // 0 = no cap
   return static_cast<int>(x);
 }
 
@@ -122,21 +123,22 @@ int env_int(const char* name, int fallback) {
 namespace co2 {
 
 const Tuning& tuning() {
-  static const Tuning t = [] {
-    Tuning u{};
-    // Measured optimum of resident wavefronts per compute unit for the sweep at
-    // 1.3B parameters (each wavefront holds 1 KB x (3+K) streams of loads):
-    // 8 for K <= 3, 6 for K <= 6, 5 for K <= 11, 4 beyond.
-    for (int k = 1; k <= CO2_MAX_K; ++k) {
-      const int w = k <= 3 ? 8 : k <= 6 ? 6 : k <= 11 ? 5 : 4;
-      u.sweep_waves_per_cu[k] = env_int("CO2_SWEEP_WAVES", w);
-    }
-    u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
-    u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 10);
-    u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 6);
-    return u;
-  }();
-  return t;
+  // Re-read on every launch (a handful of getenv calls): tuning runs change the
+  // variables between calls within one process.
+  thread_local Tuning u;
+  // Measured optimum of resident wavefronts per compute unit for the sweep at
+  // 1.3B parameters, averaged over several buffer placements (each wavefront
+  // holds 1 KB x (3+K) streams of loads): 8 for K <= 4, 7 for K <= 6, 6 for
+  // K <= 9, 5 for K <= 13, 4 beyond.
+  const int sweep_override = env_int("CO2_SWEEP_WAVES", -1);
+  for (int k = 1; k <= CO2_MAX_K; ++k) {
+    const int w = k <= 4 ? 8 : k <= 6 ? 7 : k <= 9 ? 6 : k <= 13 ? 5 : 4;
+    u.sweep_waves_per_cu[k] = sweep_override >= 0 ? sweep_override : w;
+  }
+  u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
+  u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 10);
+  u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 7);
+  return u;
 }
 
 unsigned throttle_lds_bytes(int waves_per_cu) {

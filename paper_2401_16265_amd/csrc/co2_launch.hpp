@@ -42,7 +42,7 @@ struct AdamArgs {
 // Resident wavefronts per compute unit each streaming kernel is capped to
 // (0 = no cap).  Defaults come from bandwidth sweeps on MI355X; the environment
 // variables CO2_SWEEP_WAVES, CO2_NORM_WAVES, CO2_ADAM_WAVES and CO2_COPY_WAVES
-// override them (read once, at the first launch) for tuning runs.
+// override them (read at every launch) for tuning runs.
 struct Tuning {
   int sweep_waves_per_cu[CO2_MAX_K + 1];
   int norm_waves_per_cu;

@@ -51,6 +51,52 @@ __device__ __forceinline__ float comp(const float4& q, int e) {
 }
 
 template <int K, bool HAS_X>
+struct SubTile {
+  float4 va, vm, vx, vd[K];
+};
+
+template <int K, bool HAS_X>
+__device__ __forceinline__ void load_sub(SubTile<K, HAS_X>& t, const float* x, const float* a_in,
+                                         const float* m, const DeltaPtrs& d, int64_t jv) {
+  t.va = ld4(a_in + jv);
+  t.vm = ld4(m + jv);
+  if (HAS_X) t.vx = ld4(x + jv);
+#pragma unroll
+  for (int k = 0; k < K; ++k) t.vd[k] = ld4(d.p[k] + jv);
+}
+
+// Update and store one 256-coordinate tile held in registers.
+template <int K, bool HAS_X>
+__device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X>& t, float* x, float* a_out,
+                                           float* m, float* dout, int64_t jv, float inv,
+                                           const SweepScalars& h, double& acc_m, double& acc_d,
+                                           int& nclip) {
+  float mc[4], xc[4], dc[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float ae = comp(t.va, e);
+    float dk[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) dk[k] = comp(t.vd[k], e);
+    if (HAS_X) {
+      dc[e] = ae - comp(t.vx, e);
+      acc_d += sq(dc[e]);
+    }
+    mc[e] = comp(t.vm, e);
+    xc[e] = outer_coord(ae, mc[e], mean_of_workers<K>(dk, h.rK), inv, h);
+    acc_m += sq(clip_coord(mc[e], h.phi));
+    nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));   // wavefront-uniform count
+  }
+  const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
+  if (HAS_X) {
+    st4(dout + jv, make_float4(dc[0], dc[1], dc[2], dc[3]));
+    st4(x + jv, xo);
+  }
+  st4(m + jv, make_float4(mc[0], mc[1], mc[2], mc[3]));
+  st4(a_out + jv, xo);
+}
+
+template <int K, bool HAS_X>
 __global__ __launch_bounds__(kWave) void fused_sweep(
     float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, float* dout,
     const float* __restrict__ inv_tab, const int64_t* __restrict__ off, int S, int64_t n,
@@ -61,44 +107,17 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
   const bool full = base + kSweepTile <= n;
   const int64_t jv = base + (int64_t(lane) << 2);
 
-  // All loads of the tile first; none depends on the segment lookup.
-  float4 va, vm, vx, vd[K];
-  if (full) {
-    va = ld4(a_in + jv);
-    vm = ld4(m + jv);
-    if (HAS_X) vx = ld4(x + jv);
-#pragma unroll
-    for (int k = 0; k < K; ++k) vd[k] = ld4(d.p[k] + jv);
-  }
+  // The tile's loads go out before the segment lookup, which does not depend
+  // on them and runs while they are in flight.
+  SubTile<K, HAS_X> cur;
+  if (full) load_sub<K, HAS_X>(cur, x, a_in, m, d, jv);
   const int s_lo = seg_of(off, S, base);
 
   if (full && base + kSweepTile <= off[s_lo + 1]) {
     const float inv = inv_tab[s_lo];
-    float mc[4], xc[4], dc[4];
     double acc_m = 0.0, acc_d = 0.0;
-    int nclip = 0;                                  // wavefront-uniform
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float ae = comp(va, e);
-      float dk[K];
-#pragma unroll
-      for (int k = 0; k < K; ++k) dk[k] = comp(vd[k], e);
-      if (HAS_X) {
-        dc[e] = ae - comp(vx, e);
-        acc_d += sq(dc[e]);
-      }
-      mc[e] = comp(vm, e);
-      xc[e] = outer_coord(ae, mc[e], mean_of_workers<K>(dk, h.rK), inv, h);
-      acc_m += sq(clip_coord(mc[e], h.phi));
-      nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));
-    }
-    const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
-    if (HAS_X) {
-      st4(dout + jv, make_float4(dc[0], dc[1], dc[2], dc[3]));
-      st4(x + jv, xo);
-    }
-    st4(m + jv, make_float4(mc[0], mc[1], mc[2], mc[3]));
-    st4(a_out + jv, xo);
+    int nclip = 0;
+    finish_sub<K, HAS_X>(cur, x, a_out, m, dout, jv, inv, h, acc_m, acc_d, nclip);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);

@@ -28,15 +28,48 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+_ENTRY_POINTS = ("co2_oracle_sqnorms", "co2_oracle_outer_step_f32", "co2_oracle_outer_step_f64",
+                 "co2_oracle_adamw_f32", "co2_oracle_adamw_f64")
+
+
+def _open(path):
+    lib = C.CDLL(path)
+    for name in _ENTRY_POINTS:
+        getattr(lib, name).restype = C.c_int
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
-        for name in ("co2_oracle_sqnorms", "co2_oracle_outer_step_f32",
-                     "co2_oracle_outer_step_f64", "co2_oracle_adamw_f32",
-                     "co2_oracle_adamw_f64"):
-            getattr(_lib, name).restype = C.c_int
+        _lib = _open(build())
     return _lib
+
+
+class use_library:
+    """Context manager for tests of the pins themselves: route every call of this
+    module to another build of the oracle source (e.g. one with a planted mistake)."""
+
+    def __init__(self, path):
+        self.path = path
+
+    def __enter__(self):
+        global _lib
+        self.saved = _lib
+        _lib = _open(self.path)
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
+
+
+def compile_source(src_path: str, out_path: str) -> str:
+    """Compile an oracle source file (the real one or a mutated copy) with the real flags."""
+    subprocess.run(["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+                    "-shared", "-o", out_path, src_path], check=True)
+    return out_path
 
 
 def _ptr(a, dtype):

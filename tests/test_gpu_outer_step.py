@@ -267,10 +267,20 @@ def test_1p3b_headline_size_sampled(dev):
         print(f"  1p3b step {h.t} flags={flags}", flush=True)
         res = h.step(flags=flags)
         print("   ", res, "nclipped(sample)=", h.last["nclipped"], flush=True)
-    # Lambda of ALL segments against oracle norms of the full momentum / own delta
-    # buffers is covered per sampled segment above; here: every Lambda >= 1
     lam = h.lam.cpu().numpy()
     assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
+    # Norms of ALL 292 segments at full size: the norms entry point against the
+    # oracle's ascending fp64 sums over the whole momentum and own-delta buffers.
+    from oracle import co2_oracle
+    own = h.own[h.t % 2]
+    out = torch.empty(2, h.S, dtype=torch.float64, device=dev)
+    p = co2.make_params(h.seg, hp.K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, h.t)
+    co2.co2_pseudo_grad_norms(p, [own], h.m, out, h.ws)
+    got = out.cpu().numpy()
+    print("  full-size norms of all segments vs oracle", flush=True)
+    assert_close(got[0], co2_oracle.sqnorms(own.cpu().numpy(), table), "sum of d0^2, all segments", tol=1e-12)
+    assert_close(got[1], co2_oracle.sqnorms(h.m.cpu().numpy(), table, phi=hp.phi),
+                 "sum of Clip(m)^2, all segments", tol=1e-12)
 
 
 # ------------------------------------------------------------------ config 4, ZeRO-style shard

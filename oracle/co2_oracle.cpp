@@ -243,6 +243,108 @@ int co2_oracle_outer_step_f64(int64_t n, int32_t S, const int64_t* seg_off,
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Reduced-precision transport of the pseudo-gradients (the paper's Section 2,
+// "Efficient Communication": compression of what the all-reduce carries is
+// orthogonal to CO2 and can be combined with it).  The K incoming
+// pseudo-gradients and the outgoing one are stored as bf16; all arithmetic stays
+// fp32/fp64 exactly as above.
+
+// fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays NaN (quiet).
+uint16_t co2_oracle_f32_to_bf16(float f) {
+  union { float f; uint32_t u; } cv;
+  cv.f = f;
+  uint32_t u = cv.u;
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+  const uint32_t lsb = (u >> 16) & 1u;          // last kept bit decides ties
+  u += 0x7fffu + lsb;
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// bf16 bit pattern -> fp32, exact.
+float co2_oracle_bf16_to_f32(uint16_t b) {
+  union { float f; uint32_t u; } cv;
+  cv.u = static_cast<uint32_t>(b) << 16;
+  return cv.f;
+}
+
+// One outer update with bf16 pseudo-gradient buffers: identical to
+// co2_oracle_outer_step_f32 except that
+//   d[k][j]  are bf16 bit patterns, widened exactly before use,
+//   dout[j]  = bf16(a[j] - x[j])  (fp32 subtraction, then rounded once),
+// and the own-delta norm of the NULL-first_step_norm case is taken over the
+// widened values of d[0].
+int co2_oracle_outer_step_bf16(int64_t n, int32_t S, const int64_t* seg_off,
+                               int32_t K, float alpha, float beta, float phi,
+                               float c, int32_t tau, int64_t step,
+                               float* x, const float* a_in, float* a_out,
+                               float* m, const uint16_t* const* d, uint16_t* dout,
+                               const float* first_step_norm,
+                               float* lambda_out, int64_t* nclipped) {
+  if (check_table(n, S, seg_off) || !a_in || !a_out || !m) return -1;
+  if ((x == nullptr) != (dout == nullptr)) return -1;
+  if (K < 1 || tau < 1 || !(phi > 0.0f) || step < 0) return -1;
+  if (nclipped) *nclipped = 0;
+
+  if (step == 0) {
+    for (int64_t j = 0; j < n; ++j) {
+      float aj = a_in[j];
+      if (x) { dout[j] = co2_oracle_f32_to_bf16(aj - x[j]); x[j] = aj; }
+      a_out[j] = aj;
+    }
+    if (lambda_out) for (int32_t s = 0; s < S; ++s) lambda_out[s] = 1.0f;
+    return 0;
+  }
+  if (!d) return -1;
+  for (int32_t k = 0; k < K; ++k) if (!d[k]) return -1;
+
+  const float rK = static_cast<float>(1.0 / static_cast<double>(K));
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t lo = seg_off[s], hi = seg_off[s + 1];
+    double M2 = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      double cm = static_cast<double>(clip_coord<float>(m[j], phi));
+      M2 += cm * cm;
+    }
+    double T;
+    if (first_step_norm) {
+      T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
+    } else {
+      double P2 = 0.0;
+      for (int64_t j = lo; j < hi; ++j) {
+        double dv = static_cast<double>(co2_oracle_bf16_to_f32(d[0][j]));
+        P2 += dv * dv;
+      }
+      T = std::sqrt(P2);
+    }
+    double Lam = 1.0;
+    if (c != 0.0f && T != 0.0) {
+      Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * std::sqrt(M2) / T + 1.0;
+    }
+    const float inv = static_cast<float>(1.0 / Lam);
+    if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+
+    for (int64_t j = lo; j < hi; ++j) {
+      const float aj = a_in[j];
+      if (x) dout[j] = co2_oracle_f32_to_bf16(aj - x[j]);
+      float sum = co2_oracle_bf16_to_f32(d[0][j]);
+      for (int32_t k = 1; k < K; ++k) sum = sum + co2_oracle_bf16_to_f32(d[k][j]);
+      const float dbar = sum * rK;
+      const float bm = beta * m[j];
+      const float pen = dbar * inv;
+      const float mt = bm + pen;
+      const float cm = clip_coord<float>(mt, phi);
+      const float stepv = alpha * cm;
+      const float xn = aj - stepv;
+      if (nclipped && (mt > phi || mt < -phi)) ++*nclipped;
+      m[j] = mt;
+      if (x) x[j] = xn;
+      a_out[j] = xn;
+    }
+  }
+  return 0;
+}
+
 // Local update with AdamW as the base optimizer (decoupled weight decay,
 // Loshchilov & Hutter): for inner step index k >= 1
 //   m1 <- b1*m1 + (1-b1)*g ;  v <- b2*v + (1-b2)*g*g

@@ -29,13 +29,17 @@ def build(force: bool = False) -> str:
 
 
 _ENTRY_POINTS = ("co2_oracle_sqnorms", "co2_oracle_outer_step_f32", "co2_oracle_outer_step_f64",
-                 "co2_oracle_adamw_f32", "co2_oracle_adamw_f64")
+                 "co2_oracle_outer_step_bf16", "co2_oracle_adamw_f32", "co2_oracle_adamw_f64")
 
 
 def _open(path):
     lib = C.CDLL(path)
     for name in _ENTRY_POINTS:
         getattr(lib, name).restype = C.c_int
+    lib.co2_oracle_f32_to_bf16.restype = C.c_uint16
+    lib.co2_oracle_f32_to_bf16.argtypes = [C.c_float]
+    lib.co2_oracle_bf16_to_f32.restype = C.c_float
+    lib.co2_oracle_bf16_to_f32.argtypes = [C.c_uint16]
     return lib
 
 
@@ -157,6 +161,45 @@ def outer_step_f64(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
     if rc:
         raise ValueError("co2_oracle_outer_step_f64 rejected its arguments")
     return dict(dout=dout, lam=lam)
+
+
+def f32_to_bf16(values):
+    """fp32 array -> bf16 bit patterns (uint16), element by element through the C loop."""
+    lib = _load()
+    v = np.asarray(values, dtype=np.float32).ravel()
+    return np.array([lib.co2_oracle_f32_to_bf16(C.c_float(f)) for f in v], dtype=np.uint16)
+
+
+def bf16_to_f32(bits):
+    lib = _load()
+    b = np.asarray(bits, dtype=np.uint16).ravel()
+    return np.array([lib.co2_oracle_bf16_to_f32(int(x)) for x in b], dtype=np.float32)
+
+
+def outer_step_bf16(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
+                    a_out=None, first_step_norm=None):
+    """Outer update with bf16 pseudo-gradient buffers (uint16 bit patterns).
+    Returns dict(dout (uint16), lam, nclipped)."""
+    lib = _load()
+    n = a.size
+    t, S = _table(n, seg_off)
+    if a_out is None:
+        a_out = a
+    dout = np.empty(n, dtype=np.uint16) if x is not None else None
+    lam = np.empty(S, dtype=np.float32)
+    ncl = C.c_int64(0)
+    K = len(deltas) if deltas is not None else 1
+    dptr = _ptr_array(deltas, np.uint16) if deltas is not None else None
+    rc = lib.co2_oracle_outer_step_bf16(
+        C.c_int64(n), C.c_int32(S), _ptr(t, np.int64), C.c_int32(K),
+        C.c_float(alpha), C.c_float(beta), C.c_float(phi), C.c_float(c),
+        C.c_int32(tau), C.c_int64(step),
+        _ptr(x, np.float32), _ptr(a, np.float32), _ptr(a_out, np.float32),
+        _ptr(m, np.float32), dptr, _ptr(dout, np.uint16),
+        _ptr(first_step_norm, np.float32), _ptr(lam, np.float32), C.byref(ncl))
+    if rc:
+        raise ValueError("co2_oracle_outer_step_bf16 rejected its arguments")
+    return dict(dout=dout, lam=lam, nclipped=ncl.value)
 
 
 def adamw_f32(*, p_in, p_out, grad_bf16, exp_avg, exp_avg_sq, lr, beta1, beta2,

@@ -412,3 +412,50 @@ def test_p10_adamw_epilogues_and_lr_zero(oracle):
     oracle.adamw_f32(p_in=p0, p_out=p2, grad_bf16=bits, exp_avg=np.zeros(n, np.float32),
                      exp_avg_sq=np.zeros(n, np.float32), lr=0.0, k=1, **hp)
     np.testing.assert_array_equal(p2, p0)
+
+
+# ---------------------------------------------------------------- bf16 transport
+def test_bf16_rounding_against_library_cast(oracle):
+    """The oracle's fp32->bf16 (nearest, ties to even) against torch's cast, on
+    random values, exact ties in both directions, the largest finite values,
+    denormals, zeros and infinities."""
+    r = np.random.default_rng(20)
+    vals = list(r.normal(0, 1e-3, 2000).astype(np.float32)) + list(r.normal(0, 1e3, 500).astype(np.float32))
+    bits = np.array([0x3F808000, 0x3F818000, 0x3F807FFF, 0x3F808001, 0xBF808000, 0xBF818000,
+                     0x7F7FFFFF, 0x7F7F8000, 0x7F7F7FFF, 0x00000001, 0x00008000, 0x00018000,
+                     0x807FFFFF, 0x00000000, 0x80000000, 0x7F800000, 0xFF800000], dtype=np.uint32)
+    vals += list(bits.view(np.float32))
+    v = np.array(vals, dtype=np.float32)
+    want = torch.tensor(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.f32_to_bf16(v)
+    np.testing.assert_array_equal(got, want)
+    back = oracle.bf16_to_f32(got)
+    np.testing.assert_array_equal(back, torch.tensor(v).to(torch.bfloat16).to(torch.float32).numpy())
+    nan = oracle.f32_to_bf16(np.array([np.nan], np.float32))
+    assert np.isnan(oracle.bf16_to_f32(nan)[0])
+
+
+@pytest.mark.parametrize("fsn", [False, True])
+def test_bf16_step_equals_f32_step_on_widened_inputs(oracle, fsn):
+    """With bf16 buffers the update is the fp32 update applied to the widened
+    deltas (bit for bit), and delta_out is the fp32 delta rounded once."""
+    n, K = 3000, 5
+    seg = [0, 7, 7, 1500, n]
+    a, x, m, d = rng_state(21, n, K)
+    to_bits = lambda v: torch.tensor(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)  # noqa: E731
+    widen = lambda b: torch.tensor(b.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()  # noqa: E731
+    d_bits = [to_bits(v) for v in d]
+    d_wide = [widen(b) for b in d_bits]
+    fs = f32([0.01, 0.02, 0.03, 0.04]) if fsn else None
+    kw = dict(seg_off=seg, alpha=0.9, beta=0.9, phi=5e-3, c=1.0, tau=3, first_step_norm=fs)
+    for step in (0, 1):
+        a1, x1, m1 = a.copy(), x.copy(), m.copy()
+        o1 = oracle.outer_step_f32(x=x1, a=a1, m=m1, deltas=d_wide if step else None, step=step, **kw)
+        a2, x2, m2 = a.copy(), x.copy(), m.copy()
+        o2 = oracle.outer_step_bf16(x=x2, a=a2, m=m2, deltas=d_bits if step else None, step=step, **kw)
+        np.testing.assert_array_equal(a1, a2)
+        np.testing.assert_array_equal(x1, x2)
+        np.testing.assert_array_equal(m1, m2)
+        np.testing.assert_array_equal(o1["lam"], o2["lam"])
+        assert o1["nclipped"] == o2["nclipped"]
+        np.testing.assert_array_equal(o2["dout"], to_bits(o1["dout"]))

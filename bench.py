@@ -42,6 +42,9 @@ def parse():
                          "previous round's sweep); two_pass: separate norm pass every round")
     ap.add_argument("--workload", default="1p3b")
     ap.add_argument("--K", type=int, default=0, help="override the workload's worker count")
+    ap.add_argument("--deltas", choices=["f32", "bf16"], default="f32",
+                    help="storage type of the K pseudo-gradient buffers and of delta_out "
+                         "(bf16: reduced-precision transport, co2_outer_step_bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
     return ap.parse_args()
@@ -180,25 +183,30 @@ def main():
 
     # ---- resident state: params, anchor, momentum, K-1 peers, 2 own (ping-pong)
     a = torch.empty(n, **f32); m = torch.empty(n, **f32); x = torch.empty(n, **f32)
-    own = [torch.empty(n, **f32), torch.empty(n, **f32)]
-    peers = [torch.empty(n, **f32) for _ in range(K - 1)]
+    bf16 = args.deltas == "bf16"
+    dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
+    own = [torch.empty(n, **dd), torch.empty(n, **dd)]
+    peers = [torch.empty(n, **dd) for _ in range(K - 1)]
     lam = torch.empty(S, **f32)
     ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
     student = cfg.drift == "student_t"
 
     def drift(t, bid):
         sd = co2_inputs.seed_for(cfg.seed, bid)
+        dst = x if t.dtype == torch.bfloat16 else t       # x doubles as fp32 scratch here
         if student:
-            co2_inputs.fill_student_t_(t, cfg.drift_scale, cfg.drift_nu, sd)
+            co2_inputs.fill_student_t_(dst, cfg.drift_scale, cfg.drift_nu, sd)
         else:
-            co2_inputs.fill_normal_(t, cfg.drift_scale, sd)
+            co2_inputs.fill_normal_(dst, cfg.drift_scale, sd)
+        if dst is not t:
+            t.copy_(dst)
 
     co2_inputs.fill_normal_(a, cfg.param_std, co2_inputs.seed_for(cfg.seed, 1))
     co2_inputs.fill_normal_(m, cfg.momentum_std, co2_inputs.seed_for(cfg.seed, 2))
-    drift(own[0], 100); torch.add(a, own[0], out=x)
     drift(own[1], 99)
     for k, pb in enumerate(peers):
         drift(pb, 200 + k)
+    drift(x, 100); x.add_(a)                                # local params = anchor + drift
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream().cuda_stream
@@ -211,7 +219,8 @@ def main():
         flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
                             ev[0] if ev else None, ev[1] if ev else None)
-        co2.co2_outer_step(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
+        entry = co2.co2_outer_step_bf16 if bf16 else co2.co2_outer_step
+        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
         step_no[0] += 1
 
     warmup = max(args.warmup, 2 if carried else 0)   # carried sums exist from round 2 on
@@ -229,15 +238,16 @@ def main():
 
     ms_per_step = elapsed * 1e3 / args.steps
     sweep_ms = sum(b.elapsed_ms(e) for b, e in events) / args.steps
-    sweep_bytes = (28 + 4 * K) * n                      # algorithmic bytes of one sweep launch
+    per_elem = (26 + 2 * K) if bf16 else (28 + 4 * K)   # algorithmic bytes per coordinate, one sweep
+    sweep_bytes = per_elem * n
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
 
     # ---- yardstick: plain copy kernel over one buffer pair (8 B/element)
     cb, ce = co2.HipEvent(), co2.HipEvent()
-    co2.co2_copy_f32(own[0], own[1], n, stream=stream)
+    co2.co2_copy_f32(a, x, n, stream=stream)
     cb.record(stream)
     for _ in range(5):
-        co2.co2_copy_f32(own[0], own[1], n, stream=stream)
+        co2.co2_copy_f32(a, x, n, stream=stream)
     ce.record(stream)
     ce.synchronize()
     copy_gbps = 8 * n * 5 / (cb.elapsed_ms(ce) * 1e-3) / 1e9
@@ -252,18 +262,18 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
-                               f"c={cfg.c}", "form": args.form,
-                   "step_gbps_algorithmic": (28 + 4 * K + (0 if carried else 8)) * n
+                               f"c={cfg.c}", "form": args.form, "deltas": args.deltas,
+                   "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.form)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.form)) if not bf16 and not args.K else None,
                      "kernel": "fused_sweep", "kernel_ms": sweep_ms,
                      "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
     }
     del a, m, x, own, peers
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline(cfg, table, args.cpu_sample_elems, dev)
     print(json.dumps(out))
 

@@ -135,6 +135,25 @@ int co2_outer_step(const co2_params* p,
                    const float* first_step_norm, float* lambda_out,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same update with the pseudo-gradients transported in bf16 (the paper's
+ * Section 2, "Efficient Communication": compression of what the all-reduce
+ * carries is orthogonal to CO2 and can be combined with it).  Differences from
+ * co2_outer_step:
+ *   deltas_bf16     HOST array of K DEVICE uint16[n] pointers, bf16 bit patterns,
+ *                   widened exactly to fp32 before the (fp32) mean;
+ *   delta_out_bf16  DEVICE uint16[n]: bf16(anchor - params), the fp32 difference
+ *                   rounded once to nearest-even; the sum of squares carried to
+ *                   the next round is taken over these rounded values.
+ * Everything else (arithmetic order, Lambda, flags, errors) is unchanged.  26+2K
+ * bytes per coordinate instead of 28+4K.  Carried sums (CO2_FLAG_CARRIED_NORMS)
+ * must come from a previous call of this same entry point. */
+int co2_outer_step_bf16(const co2_params* p,
+                        float* params, const float* anchor, float* anchor_out,
+                        float* momentum, const uint16_t* const* deltas_bf16,
+                        uint16_t* delta_out_bf16,
+                        const float* first_step_norm, float* lambda_out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Segmented sums of squares (the quantities under the roots of Eq. 3's norms).
  * Uses p->n, p->S, p->seg_off, p->seg_off_dev and p->clip_phi only.
  *

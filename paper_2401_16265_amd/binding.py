@@ -58,6 +58,8 @@ def lib() -> C.CDLL:
         L.co2_last_hip_error.argtypes = []
         L.co2_outer_step.restype = C.c_int
         L.co2_outer_step.argtypes = [C.POINTER(Co2Params)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        L.co2_outer_step_bf16.restype = C.c_int
+        L.co2_outer_step_bf16.argtypes = L.co2_outer_step.argtypes
         L.co2_pseudo_grad_norms.restype = C.c_int
         L.co2_pseudo_grad_norms.argtypes = [C.POINTER(Co2Params), C.c_void_p, C.c_int32, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -199,6 +201,30 @@ def co2_outer_step(p: Co2Params, params, anchor, anchor_out, momentum, deltas, d
         _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream))
     return _check(rc, "co2_outer_step", check)
+
+
+def _bf16_ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if t.dtype not in (torch.bfloat16, torch.uint16, torch.int16):
+        raise ValueError("expected a tensor of bf16 values / bit patterns")
+    return _dp(t)
+
+
+def co2_outer_step_bf16(p: Co2Params, params, anchor, anchor_out, momentum, deltas_bf16,
+                        delta_out_bf16, first_step_norm, lambda_out, workspace, stream=None,
+                        check: bool = True) -> int:
+    """int co2_outer_step_bf16(...) -- see include/co2.h.  Delta tensors are torch.bfloat16."""
+    f32 = torch.float32
+    dptrs = None
+    if deltas_bf16 is not None:
+        dptrs = (C.c_void_p * len(deltas_bf16))(*[_bf16_ptr(d) for d in deltas_bf16])
+    rc = lib().co2_outer_step_bf16(
+        C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),
+        dptrs, _bf16_ptr(delta_out_bf16), _dp(first_step_norm, f32), _dp(lambda_out, f32),
+        _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    return _check(rc, "co2_outer_step_bf16", check)
 
 
 def co2_pseudo_grad_norms(p: Co2Params, bufs, momentum, sqnorm_out, workspace, stream=None,

@@ -170,10 +170,16 @@ const char* co2_strerror(int code) {
 
 int co2_last_hip_error(void) { return g_last_hip_error; }
 
-int co2_outer_step(const co2_params* p, float* params, const float* anchor, float* anchor_out,
-                   float* momentum, const float* const* deltas, float* delta_out,
-                   const float* first_step_norm, float* lambda_out, void* workspace,
-                   size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Shared by co2_outer_step (fp32 pseudo-gradient buffers) and co2_outer_step_bf16
+// (bf16 bit patterns): delta_elem is the byte size of one stored pseudo-gradient.
+int outer_step_impl(const co2_params* p, float* params, const float* anchor, float* anchor_out,
+                    float* momentum, const void* const* deltas, void* delta_out, bool bf16,
+                    const float* first_step_norm, float* lambda_out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
   // ---- validation (no side effects before it passes)
   if (!p) return CO2_EINVAL;
   if (!table_ok(p->n, p->S, p->seg_off) || !p->seg_off_dev) return CO2_EINVAL;
@@ -191,12 +197,14 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   // Carried sums of delta_out^2 exist only if the previous call formed delta_out.
   if (carried && !first_step_norm && !params) return CO2_EINVAL;
   const size_t nb = sizeof(float) * static_cast<size_t>(p->n);
+  const size_t db = (bf16 ? sizeof(uint16_t) : sizeof(float)) * static_cast<size_t>(p->n);
   const size_t sb = sizeof(float) * static_cast<size_t>(p->S);
   const void* vec[5] = {params, anchor, momentum, delta_out, anchor_out == anchor ? nullptr : anchor_out};
+  const size_t vecb[5] = {nb, nb, nb, db, nb};
   for (int i = 0; i < 5; ++i) {
     if (!aligned16(vec[i])) return CO2_EINVAL;
     for (int j = i + 1; j < 5; ++j)
-      if (overlaps(vec[i], nb, vec[j], nb)) return CO2_EINVAL;
+      if (overlaps(vec[i], vecb[i], vec[j], vecb[j])) return CO2_EINVAL;
   }
   if (!aligned16(p->seg_off_dev) || !aligned16(first_step_norm) || !aligned16(lambda_out) ||
       !aligned16(p->clipped_out))
@@ -206,11 +214,11 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   if (!first) {
     if (!deltas) return CO2_EINVAL;
     for (int k = 0; k < p->K; ++k) {
-      const float* dk = deltas[k];
+      const void* dk = deltas[k];
       if (!dk || !aligned16(dk)) return CO2_EINVAL;
       // inputs may repeat among themselves, but no output may touch them
-      if (overlaps(dk, nb, params, nb) || overlaps(dk, nb, momentum, nb) ||
-          overlaps(dk, nb, delta_out, nb) || overlaps(dk, nb, anchor_out, nb))
+      if (overlaps(dk, db, params, nb) || overlaps(dk, db, momentum, nb) ||
+          overlaps(dk, db, delta_out, db) || overlaps(dk, db, anchor_out, nb))
         return CO2_EINVAL;
       dptr.p[k] = dk;
     }
@@ -218,12 +226,12 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
   const Workspace w = layout(workspace, p->n, p->S);
   if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
   for (int i = 0; i < 5; ++i)
-    if (overlaps(vec[i], nb, workspace, w.bytes)) return CO2_EINVAL;
+    if (overlaps(vec[i], vecb[i], workspace, w.bytes)) return CO2_EINVAL;
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   co2::SweepArgs g{};
   g.x = params; g.a_in = anchor; g.a_out = anchor_out; g.m = momentum; g.d = dptr;
-  g.dout = delta_out; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
+  g.dout = delta_out; g.bf16 = bf16; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
   g.alpha = p->alpha; g.beta = p->beta; g.phi = p->clip_phi;
   g.rK = static_cast<float>(1.0 / static_cast<double>(p->K));
   g.slots = w.slots;
@@ -246,8 +254,8 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
     e = enqueue_lambda(w, co2::kSweepTile, p, first_step_norm, lambda_out, st);
   } else {
     e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, p->clip_phi,
-                                    need_d0 ? dptr.p[0] : nullptr, 0.0f, p->seg_off_dev, p->S,
-                                    p->n, w.slots, st);
+                                    need_d0 ? dptr.p[0] : nullptr, 0.0f, bf16, p->seg_off_dev,
+                                    p->S, p->n, w.slots, st);
     if (e != hipSuccess) return fail_hip(e);
     e = enqueue_lambda(w, co2::kNormTile, p, first_step_norm, lambda_out, st);
   }
@@ -261,6 +269,29 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
     return fail_hip(e);
   if (p->clipped_out && (e = enqueue_counts(w, p, st)) != hipSuccess) return fail_hip(e);
   return CO2_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int co2_outer_step(const co2_params* p, float* params, const float* anchor, float* anchor_out,
+                   float* momentum, const float* const* deltas, float* delta_out,
+                   const float* first_step_norm, float* lambda_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  return outer_step_impl(p, params, anchor, anchor_out, momentum,
+                         reinterpret_cast<const void* const*>(deltas), delta_out, false,
+                         first_step_norm, lambda_out, workspace, workspace_bytes, hip_stream);
+}
+
+int co2_outer_step_bf16(const co2_params* p, float* params, const float* anchor,
+                        float* anchor_out, float* momentum, const uint16_t* const* deltas_bf16,
+                        uint16_t* delta_out_bf16, const float* first_step_norm,
+                        float* lambda_out, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  return outer_step_impl(p, params, anchor, anchor_out, momentum,
+                         reinterpret_cast<const void* const*>(deltas_bf16), delta_out_bf16, true,
+                         first_step_norm, lambda_out, workspace, workspace_bytes, hip_stream);
 }
 
 int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t nbuf,
@@ -294,8 +325,8 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
     const float phi0 = r < nbuf ? 0.0f : p->clip_phi;
     const float* b1 = pair ? (r + 1 < nbuf ? bufs[r + 1] : momentum) : nullptr;
     const float phi1 = pair ? (r + 1 < nbuf ? 0.0f : p->clip_phi) : 0.0f;
-    hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, p->seg_off_dev,
-                                               p->S, p->n, w.slots, st);
+    hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, false,
+                                               p->seg_off_dev, p->S, p->n, w.slots, st);
     if (e != hipSuccess) return fail_hip(e);
     e = enqueue_totals(w, w.slots, 0, co2::kNormTile, p->seg_off_dev, p->S,
                        sqnorm_out + static_cast<size_t>(r) * p->S, st);

@@ -39,8 +39,10 @@ struct alignas(32) SlotRec {
   double v[4];
 };
 
+// The K workers' pseudo-gradient buffers: fp32, or bf16 bit patterns for the
+// reduced-precision transport variant.
 struct DeltaPtrs {
-  const float* p[CO2_MAX_K];
+  const void* p[CO2_MAX_K];
 };
 
 // Section 3.3: Clip(chi, phi) = max{-phi, min{chi, phi}}.
@@ -124,6 +126,75 @@ __device__ __forceinline__ void st4(float* p, float4 v) {
   const v4f t = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
 }
+
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+// fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+
+// How a pseudo-gradient buffer is read and written: four coordinates per lane
+// as one vector access, or one coordinate at a time on the element-wise path.
+// `stored(d)` is the value a reader of the buffer will see after `d` is written.
+template <bool BF16>
+struct DeltaIO;
+
+template <>
+struct DeltaIO<false> {
+  using Vec = float4;
+  static __device__ __forceinline__ Vec load4(const void* p, int64_t j) {
+    return ld4(static_cast<const float*>(p) + j);
+  }
+  static __device__ __forceinline__ float get(const Vec& v, int e) {
+    return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+  }
+  static __device__ __forceinline__ float load1(const void* p, int64_t j) {
+    return static_cast<const float*>(p)[j];
+  }
+  static __device__ __forceinline__ float stored(float d) { return d; }
+  static __device__ __forceinline__ void store4(void* p, int64_t j, const float (&d)[4]) {
+    st4(static_cast<float*>(p) + j, make_float4(d[0], d[1], d[2], d[3]));
+  }
+  static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
+    static_cast<float*>(p)[j] = d;
+  }
+};
+
+template <>
+struct DeltaIO<true> {
+  using Vec = uint2;
+  static __device__ __forceinline__ Vec load4(const void* p, int64_t j) {
+    const v2u t = __builtin_nontemporal_load(
+        reinterpret_cast<const v2u*>(static_cast<const uint16_t*>(p) + j));
+    return make_uint2(t.x, t.y);
+  }
+  static __device__ __forceinline__ float get(const Vec& v, int e) {
+    const uint32_t w = e < 2 ? v.x : v.y;
+    return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  static __device__ __forceinline__ float load1(const void* p, int64_t j) {
+    return bf16_bits_to_f32(static_cast<const uint16_t*>(p)[j]);
+  }
+  static __device__ __forceinline__ float stored(float d) {
+    return bf16_bits_to_f32(f32_to_bf16_bits(d));
+  }
+  // d[] already holds representable values (stored()), so the shift is exact
+  static __device__ __forceinline__ void store4(void* p, int64_t j, const float (&d)[4]) {
+    const v2u t = {(__float_as_uint(d[0]) >> 16) | (__float_as_uint(d[1]) & 0xffff0000u),
+                   (__float_as_uint(d[2]) >> 16) | (__float_as_uint(d[3]) & 0xffff0000u)};
+    __builtin_nontemporal_store(t, reinterpret_cast<v2u*>(static_cast<uint16_t*>(p) + j));
+  }
+  static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
+    static_cast<uint16_t*>(p)[j] = static_cast<uint16_t>(__float_as_uint(d) >> 16);
+  }
+};
 
 __device__ __forceinline__ double sq(float v) {
   const double d = static_cast<double>(v);

@@ -13,8 +13,9 @@ struct SweepArgs {
   const float* a_in;        // anchor
   float* a_out;             // next anchor (may equal a_in)
   float* m;                 // momentum
-  DeltaPtrs d;              // K worker pseudo-gradients
-  float* dout;              // delta_out (nullable with x)
+  DeltaPtrs d;              // K worker pseudo-gradients (fp32, or bf16 bits if bf16)
+  void* dout;               // delta_out (nullable with x), same element type as d
+  bool bf16;                // pseudo-gradient buffers hold bf16 bit patterns
   const float* inv;         // 1/Lambda per segment
   const int64_t* off_dev;   // segment table on the device
   int S;
@@ -54,9 +55,10 @@ const Tuning& tuning();
 // `waves_per_cu` of them fit on a compute unit.
 unsigned throttle_lds_bytes(int waves_per_cu);
 
-hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
-                                  float phi1, const int64_t* off_dev, int S, int64_t n,
-                                  SlotRec* slots, hipStream_t st);
+// b1 (optional second buffer) may hold bf16 bit patterns (b1_bf16).
+hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const void* b1,
+                                  float phi1, bool b1_bf16, const int64_t* off_dev, int S,
+                                  int64_t n, SlotRec* slots, hipStream_t st);
 // Sums column `col` (and col+1 if two) of each segment's slot records into
 // out_a (and out_b), `split` sub-sums per segment.
 hipError_t launch_slot_sums(const SlotRec* slots, int col, bool two, const int64_t* off_dev,
@@ -68,7 +70,7 @@ hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S,
                                 const float* first_step_norm, float c, float alpha, int tau,
                                 double* seg_sq, float* inv, float* lambda_out, hipStream_t st);
 hipError_t launch_sqrt_to_f32(const double* sq_in, float* out, int S, hipStream_t st);
-hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t st);
+hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t st);   // g.bf16 selects the variant
 hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st);
 hipError_t launch_adamw(const AdamArgs& g, hipStream_t st);

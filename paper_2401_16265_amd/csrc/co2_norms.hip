@@ -28,10 +28,12 @@ __device__ __forceinline__ void acc4(double& acc, float4 q, float phi) {
   acc += sq(q.x); acc += sq(q.y); acc += sq(q.z); acc += sq(q.w);
 }
 
-template <int NB>
+// NB buffers (1 or 2); the second may hold bf16 bit patterns (B1_BF16).
+template <int NB, bool B1_BF16>
 __global__ __launch_bounds__(kWave) void sqnorm_partials(
-    const float* __restrict__ b0, float phi0, const float* __restrict__ b1, float phi1,
+    const float* __restrict__ b0, float phi0, const void* __restrict__ b1, float phi1,
     const int64_t* __restrict__ off, int S, int64_t n, SlotRec* __restrict__ slots) {
+  using IO1 = DeltaIO<B1_BF16>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kNormTile;
   const int lane = threadIdx.x;
@@ -39,13 +41,14 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
 
   // Loads first: they do not depend on the segment lookup below, which then
   // overlaps with them.
-  float4 q0[kNormU], q1[kNormU];
+  float4 q0[kNormU];
+  typename IO1::Vec q1[kNormU];
   if (full) {
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {
       const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
       q0[u] = ld4(b0 + j);
-      if (NB == 2) q1[u] = ld4(b1 + j);
+      if (NB == 2) q1[u] = IO1::load4(b1, j);
     }
   }
   const int s_lo = seg_of(off, S, base);
@@ -55,7 +58,10 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {
       acc4(a0, q0[u], phi0);
-      if (NB == 2) acc4(a1, q1[u], phi1);
+      if (NB == 2) {
+        acc4(a1, make_float4(IO1::get(q1[u], 0), IO1::get(q1[u], 1), IO1::get(q1[u], 2),
+                             IO1::get(q1[u], 3)), phi1);
+      }
     }
     const double t0 = wave_sum(a0);
     double t1 = 0.0;
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
       if (phi0 > 0.0f) v = clip_coord(v, phi0);
       a0 += sq(v);
       if (NB == 2) {
-        float r = b1[j];
+        float r = IO1::load1(b1, j);
         if (phi1 > 0.0f) r = clip_coord(r, phi1);
         a1 += sq(r);
       }
@@ -177,17 +183,20 @@ __global__ __launch_bounds__(kReduceBlock) void sqrt_to_f32(const double* __rest
 
 // ---------------------------------------------------------------- launches
 
-hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const float* b1,
-                                  float phi1, const int64_t* off_dev, int S, int64_t n,
-                                  SlotRec* slots, hipStream_t st) {
+hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const void* b1,
+                                  float phi1, bool b1_bf16, const int64_t* off_dev, int S,
+                                  int64_t n, SlotRec* slots, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>((n + kNormTile - 1) / kNormTile)), block(kWave);
   const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu);
-  if (nb == 2) {
-    hipLaunchKernelGGL(sqnorm_partials<2>, grid, block, lds, st, b0, phi0, b1, phi1, off_dev, S,
-                       n, slots);
+  if (nb == 2 && b1_bf16) {
+    hipLaunchKernelGGL((sqnorm_partials<2, true>), grid, block, lds, st, b0, phi0, b1, phi1,
+                       off_dev, S, n, slots);
+  } else if (nb == 2) {
+    hipLaunchKernelGGL((sqnorm_partials<2, false>), grid, block, lds, st, b0, phi0, b1, phi1,
+                       off_dev, S, n, slots);
   } else {
-    hipLaunchKernelGGL(sqnorm_partials<1>, grid, block, lds, st, b0, phi0, b0, 0.0f, off_dev, S,
-                       n, slots);
+    hipLaunchKernelGGL((sqnorm_partials<1, false>), grid, block, lds, st, b0, phi0,
+                       static_cast<const void*>(b0), 0.0f, off_dev, S, n, slots);
   }
   return hipGetLastError();
 }

@@ -50,36 +50,39 @@ __device__ __forceinline__ float comp(const float4& q, int e) {
   return e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
 }
 
-template <int K, bool HAS_X>
+template <int K, bool HAS_X, bool BF16>
 struct SubTile {
-  float4 va, vm, vx, vd[K];
+  float4 va, vm, vx;
+  typename DeltaIO<BF16>::Vec vd[K];
 };
 
-template <int K, bool HAS_X>
-__device__ __forceinline__ void load_sub(SubTile<K, HAS_X>& t, const float* x, const float* a_in,
-                                         const float* m, const DeltaPtrs& d, int64_t jv) {
+template <int K, bool HAS_X, bool BF16>
+__device__ __forceinline__ void load_sub(SubTile<K, HAS_X, BF16>& t, const float* x,
+                                         const float* a_in, const float* m, const DeltaPtrs& d,
+                                         int64_t jv) {
   t.va = ld4(a_in + jv);
   t.vm = ld4(m + jv);
   if (HAS_X) t.vx = ld4(x + jv);
 #pragma unroll
-  for (int k = 0; k < K; ++k) t.vd[k] = ld4(d.p[k] + jv);
+  for (int k = 0; k < K; ++k) t.vd[k] = DeltaIO<BF16>::load4(d.p[k], jv);
 }
 
 // Update and store one 256-coordinate tile held in registers.
-template <int K, bool HAS_X>
-__device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X>& t, float* x, float* a_out,
-                                           float* m, float* dout, int64_t jv, float inv,
-                                           const SweepScalars& h, double& acc_m, double& acc_d,
-                                           int& nclip) {
+template <int K, bool HAS_X, bool BF16>
+__device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X, BF16>& t, float* x,
+                                           float* a_out, float* m, void* dout, int64_t jv,
+                                           float inv, const SweepScalars& h, double& acc_m,
+                                           double& acc_d, int& nclip) {
+  using IO = DeltaIO<BF16>;
   float mc[4], xc[4], dc[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float ae = comp(t.va, e);
     float dk[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) dk[k] = comp(t.vd[k], e);
+    for (int k = 0; k < K; ++k) dk[k] = IO::get(t.vd[k], e);
     if (HAS_X) {
-      dc[e] = ae - comp(t.vx, e);
+      dc[e] = IO::stored(ae - comp(t.vx, e));
       acc_d += sq(dc[e]);
     }
     mc[e] = comp(t.vm, e);
@@ -89,18 +92,19 @@ __device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X>& t, float* x,
   }
   const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
   if (HAS_X) {
-    st4(dout + jv, make_float4(dc[0], dc[1], dc[2], dc[3]));
+    IO::store4(dout, jv, dc);
     st4(x + jv, xo);
   }
   st4(m + jv, make_float4(mc[0], mc[1], mc[2], mc[3]));
   st4(a_out + jv, xo);
 }
 
-template <int K, bool HAS_X>
+template <int K, bool HAS_X, bool BF16>
 __global__ __launch_bounds__(kWave) void fused_sweep(
-    float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, float* dout,
+    float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, void* dout,
     const float* __restrict__ inv_tab, const int64_t* __restrict__ off, int S, int64_t n,
     SweepScalars h, SlotRec* __restrict__ slots) {
+  using IO = DeltaIO<BF16>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int lane = threadIdx.x;
@@ -109,15 +113,15 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
 
   // The tile's loads go out before the segment lookup, which does not depend
   // on them and runs while they are in flight.
-  SubTile<K, HAS_X> cur;
-  if (full) load_sub<K, HAS_X>(cur, x, a_in, m, d, jv);
+  SubTile<K, HAS_X, BF16> cur;
+  if (full) load_sub<K, HAS_X, BF16>(cur, x, a_in, m, d, jv);
   const int s_lo = seg_of(off, S, base);
 
   if (full && base + kSweepTile <= off[s_lo + 1]) {
     const float inv = inv_tab[s_lo];
     double acc_m = 0.0, acc_d = 0.0;
     int nclip = 0;
-    finish_sub<K, HAS_X>(cur, x, a_out, m, dout, jv, inv, h, acc_m, acc_d, nclip);
+    finish_sub<K, HAS_X, BF16>(cur, x, a_out, m, dout, jv, inv, h, acc_m, acc_d, nclip);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
@@ -139,15 +143,15 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
       float mj = m[j];
       float dk[K];
 #pragma unroll
-      for (int k = 0; k < K; ++k) dk[k] = d.p[k][j];
+      for (int k = 0; k < K; ++k) dk[k] = IO::load1(d.p[k], j);
       float dj = 0.0f;
-      if (HAS_X) dj = a - x[j];
+      if (HAS_X) dj = IO::stored(a - x[j]);
       const float xn = outer_coord(a, mj, mean_of_workers<K>(dk, h.rK), inv, h);
       acc_m += sq(clip_coord(mj, h.phi));
       if (fabsf(mj) > h.phi) acc_c += 1.0;
       if (HAS_X) {
         acc_d += sq(dj);
-        dout[j] = dj;
+        IO::store1(dout, j, dj);
         x[j] = xn;
       }
       m[j] = mj;
@@ -165,10 +169,11 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
 // delta_out = anchor - params; params = anchor_out = anchor.  Also leaves the
 // sums of Clip(m,phi)^2 and delta_out^2 per slot for the next round's gap.
 // Runs once per training run, so it is kept simple (element-wise path only).
-template <bool HAS_X>
+template <bool HAS_X, bool BF16>
 __global__ __launch_bounds__(kWave) void first_round(
-    float* x, const float* a_in, float* a_out, const float* __restrict__ m, float* dout,
+    float* x, const float* a_in, float* a_out, const float* __restrict__ m, void* dout,
     const int64_t* __restrict__ off, int S, int64_t n, float phi, SlotRec* __restrict__ slots) {
+  using IO = DeltaIO<BF16>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
@@ -184,9 +189,9 @@ __global__ __launch_bounds__(kWave) void first_round(
       const float a = a_in[j];
       acc_m += sq(clip_coord(m[j], phi));
       if (HAS_X) {
-        const float dj = a - x[j];
+        const float dj = IO::stored(a - x[j]);
         acc_d += sq(dj);
-        dout[j] = dj;
+        IO::store1(dout, j, dj);
         x[j] = a;
       }
       if (a_out != a_in) a_out[j] = a;
@@ -216,19 +221,21 @@ __global__ __launch_bounds__(kWave) void copy_f32(const float* __restrict__ src,
 
 // ---------------------------------------------------------------- launches
 
+template <int K, bool HAS_X, bool BF16>
+static hipError_t launch_sweep_v(const SweepArgs& g, hipStream_t st) {
+  const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
+  // bf16 pseudo-gradients put half the bytes per stream in flight: cap like K/2 fp32 streams
+  const unsigned lds = throttle_lds_bytes(tuning().sweep_waves_per_cu[BF16 ? (K + 1) / 2 : K]);
+  const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
+  hipLaunchKernelGGL((fused_sweep<K, HAS_X, BF16>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
+                     g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
+  return hipGetLastError();
+}
+
 template <int K>
 static hipError_t launch_sweep_k(bool has_x, const SweepArgs& g, hipStream_t st) {
-  const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  const unsigned lds = throttle_lds_bytes(tuning().sweep_waves_per_cu[K]);
-  const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
-  if (has_x) {
-    hipLaunchKernelGGL((fused_sweep<K, true>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
-                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
-  } else {
-    hipLaunchKernelGGL((fused_sweep<K, false>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
-                       g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
-  }
-  return hipGetLastError();
+  if (g.bf16) return has_x ? launch_sweep_v<K, true, true>(g, st) : launch_sweep_v<K, false, true>(g, st);
+  return has_x ? launch_sweep_v<K, true, false>(g, st) : launch_sweep_v<K, false, false>(g, st);
 }
 
 hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t st) {
@@ -242,16 +249,17 @@ hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t
   }
 }
 
-hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st) {
+template <bool HAS_X, bool BF16>
+static hipError_t launch_first_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  if (has_x) {
-    hipLaunchKernelGGL(first_round<true>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in, g.a_out,
-                       g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
-  } else {
-    hipLaunchKernelGGL(first_round<false>, dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in,
-                       g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
-  }
+  hipLaunchKernelGGL((first_round<HAS_X, BF16>), dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in,
+                     g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
   return hipGetLastError();
+}
+
+hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st) {
+  if (g.bf16) return has_x ? launch_first_v<true, true>(g, st) : launch_first_v<false, true>(g, st);
+  return has_x ? launch_first_v<true, false>(g, st) : launch_first_v<false, false>(g, st);
 }
 
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st) {

@@ -56,7 +56,7 @@ class OuterStepHarness:
                  sample: Optional[Sequence[int]] = None, drift: str = "normal",
                  drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
                  momentum_std: float = 0.02, truth: bool = False, use_first_step_norm: bool = False,
-                 start_step: int = 0):
+                 start_step: int = 0, bf16: bool = False):
         self.table = list(table)
         self.n, self.S = self.table[-1], len(self.table) - 1
         self.hp, self.dev, self.seed = hp, device, seed
@@ -67,8 +67,12 @@ class OuterStepHarness:
         self.x = torch.empty(n, **f32)
         self.a = torch.empty(n, **f32)
         self.m = torch.empty(n, **f32)
-        self.own = [torch.zeros(n, **f32), torch.zeros(n, **f32)]   # ping-pong: delta_out / deltas[0]
-        self.peers = [torch.zeros(n, **f32) for _ in range(K - 1)]
+        # pseudo-gradient buffers: fp32, or bf16 for the reduced-precision transport
+        self.bf16 = bf16
+        dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+        self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]   # ping-pong: delta_out / deltas[0]
+        self.peers = [torch.zeros(n, **dd) for _ in range(K - 1)]
+        self.scratch = torch.empty(n, **f32) if bf16 else None
         self.lam = torch.empty(self.S, **f32)
         self.clipped = torch.full((self.S,), -1, dtype=torch.int64, device=device)
         self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
@@ -89,7 +93,7 @@ class OuterStepHarness:
         self.o_a = self.gather(self.a)
         self.o_m = self.gather(self.m)
         self.o_x = np.empty_like(self.o_a)
-        self.o_own = np.zeros_like(self.o_a)
+        self.o_own = np.zeros(self.o_a.size, dtype=np.uint16 if bf16 else np.float32)
         if start_step >= 1:
             # no earlier round has produced the worker's own previous
             # pseudo-gradient: draw it like a peer's
@@ -99,26 +103,38 @@ class OuterStepHarness:
 
     # -- helpers
     def gather(self, buf: torch.Tensor) -> np.ndarray:
+        """Sampled segments of a device buffer as one host array (bf16 buffers
+        come back as their uint16 bit patterns)."""
+        if buf.dtype == torch.bfloat16:
+            buf = buf.view(torch.int16)
         parts = [buf[self.table[s]:self.table[s + 1]] for s in self.sample]
-        if len(parts) == 1:
-            return parts[0].cpu().numpy().copy()
-        return torch.cat(parts).cpu().numpy()
+        out = parts[0].cpu().numpy().copy() if len(parts) == 1 else torch.cat(parts).cpu().numpy()
+        return out.view(np.uint16) if out.dtype == np.int16 else out
+
+    @staticmethod
+    def widen(bits: np.ndarray) -> np.ndarray:
+        """bf16 bit patterns -> the fp32 values they stand for (test-side, exact)."""
+        return (bits.astype(np.uint32) << 16).view(np.float32)
 
     def _fill_drift(self, t: torch.Tensor, buffer_id: int):
         sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)
+        dst = self.scratch if t.dtype == torch.bfloat16 else t
         if self.drift == "student_t":
-            co2_inputs.fill_student_t_(t, self.drift_scale, self.drift_nu, sd)
+            co2_inputs.fill_student_t_(dst, self.drift_scale, self.drift_nu, sd)
         else:
-            co2_inputs.fill_normal_(t, self.drift_scale, sd)
+            co2_inputs.fill_normal_(dst, self.drift_scale, sd)
+        if dst is not t:
+            t.copy_(dst)                      # the sender's rounding to bf16 (input synthesis)
 
     def step(self, flags: int = 0, split: bool = False, check: bool = True, events=None):
         """One outer round on both sides; returns dict of worst relative errors."""
         hp, t = self.hp, self.t
         cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]   # cur: deltas[0]; nxt: delta_out
         # inner loop stand-in: local params drift away from the anchor
-        self._fill_drift(nxt, 100)                      # scratch: overwritten by delta_out
-        torch.add(self.a, nxt, out=self.x)
-        o_noise = self.gather(nxt)
+        noise = self.scratch if self.bf16 else nxt      # nxt is overwritten by delta_out anyway
+        self._fill_drift(noise, 100)
+        torch.add(self.a, noise, out=self.x)
+        o_noise = self.gather(noise)
         self.o_x = self.o_a + o_noise                   # same fp32 add as the line above
         # peers' pseudo-gradients of the previous round (arrived through the all-reduce)
         o_peers = []
@@ -137,18 +153,17 @@ class OuterStepHarness:
                             ev_b, ev_e, self.clipped)
         deltas = [cur] + self.peers
         a_out = self.a
+        entry = co2.co2_outer_step_bf16 if self.bf16 else co2.co2_outer_step
         if split:
             # side-stream form: m and the next anchor only; the boundary work
             # (delta_out, params) is done by the caller
             a_out = torch.empty_like(self.a)
-            co2.co2_outer_step(p, None, self.a, a_out, self.m, deltas, None, self.fsn, self.lam,
-                               self.ws)
-            torch.sub(self.a, self.x, out=nxt)
+            entry(p, None, self.a, a_out, self.m, deltas, None, self.fsn, self.lam, self.ws)
+            nxt.copy_(torch.sub(self.a, self.x))
             self.x.copy_(a_out)
             self.a.copy_(a_out)
         else:
-            co2.co2_outer_step(p, self.x, self.a, self.a, self.m, deltas, nxt, self.fsn, self.lam,
-                               self.ws)
+            entry(p, self.x, self.a, self.a, self.m, deltas, nxt, self.fsn, self.lam, self.ws)
 
         # ---- all-fp64 evaluation of this one round, from the fp32 oracle's state
         # before the round (rounding errors of earlier rounds are part of that
@@ -158,7 +173,8 @@ class OuterStepHarness:
         if self.truth:
             self.t_a, self.t_m = self.o_a.astype(np.float64), self.o_m.astype(np.float64)
             t_x = self.o_x.astype(np.float64)
-            t_d = ([self.o_own.astype(np.float64)] + [v.astype(np.float64) for v in o_peers]
+            val = self.widen if self.bf16 else (lambda v: v)
+            t_d = ([val(self.o_own).astype(np.float64)] + [val(v).astype(np.float64) for v in o_peers]
                    if t >= 1 else None)
             self._truth_prev = (self.t_a.copy(), self.t_m.copy(), t_d)
             self.last_truth = co2_oracle.outer_step_f64(
@@ -169,8 +185,8 @@ class OuterStepHarness:
         kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
                   tau=hp.tau, step=t)
         o_d = [self.o_own] + o_peers if t >= 1 else None
-        out = co2_oracle.outer_step_f32(x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d,
-                                        first_step_norm=o_fsn, **kw)
+        oracle_step = co2_oracle.outer_step_bf16 if self.bf16 else co2_oracle.outer_step_f32
+        out = oracle_step(x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d, first_step_norm=o_fsn, **kw)
         self.o_own = out["dout"]
         self.last = out
         res = {}
@@ -187,7 +203,11 @@ class OuterStepHarness:
         res["params"] = assert_close(g_x, self.o_x, "params")
         res["anchor"] = assert_close(g_a, self.o_a, "anchor")
         res["momentum"] = assert_close(g_m, self.o_m, "momentum")
-        res["delta_out"] = assert_close(g_d, self.o_own, "delta_out")
+        if self.bf16:
+            assert np.array_equal(g_d, self.o_own), "delta_out (bf16 bit patterns) differs"
+            res["delta_out"] = 0.0
+        else:
+            res["delta_out"] = assert_close(g_d, self.o_own, "delta_out")
         res["bit_exact"] = bool(np.array_equal(g_x, self.o_x) and np.array_equal(g_m, self.o_m)
                                 and np.array_equal(g_d, self.o_own) and np.array_equal(g_a, self.o_a))
         # per-segment count of clamped coordinates (integers: exact)

@@ -167,3 +167,16 @@ def test_package_does_not_import_the_oracle():
             "bad=[m for m in sys.modules if m.startswith('oracle')]; sys.exit(1 if bad else 0)")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     assert subprocess.run([sys.executable, "-c", code], cwd=root).returncode == 0
+
+
+def test_outer_step_bf16_validates_like_the_fp32_entry():
+    p, keep = _params([0, 1000, 4096])
+    L = co2.lib()
+    dp = (C.c_void_p * 2)(_fake(3), _fake(4))
+    ok_args = [C.byref(p), _fake(0), _fake(1), _fake(1), _fake(2), dp, _fake(5), None, None, _fake(8), 1 << 19, None]
+    bad = list(ok_args); bad[6] = None                       # delta_out missing
+    assert L.co2_outer_step_bf16(*bad) == co2.CO2_EINVAL
+    bad = list(ok_args); bad[6] = _fake(3) + 4096            # overlaps deltas[0] (2-byte elements: 8 KiB)
+    assert L.co2_outer_step_bf16(*bad) == co2.CO2_EINVAL
+    bad = list(ok_args); bad[9] = None
+    assert L.co2_outer_step_bf16(*bad) == co2.CO2_EWORKSPACE

@@ -128,6 +128,42 @@ def test_multi_step_ragged_table(dev, mode):
     assert h.last["nclipped"] > 0
 
 
+# ------------------------------------------------------------------ bf16 transport of the deltas
+@pytest.mark.parametrize("mode", ["two_pass", "carried", "split"])
+def test_bf16_deltas_multi_step(dev, mode):
+    table = co2_inputs.gpt_table(layers=3, d=97, ffn=385, vocab=3001, ctx=63)
+    h = OuterStepHarness(table, HP(K=8, beta=0.95, phi=2e-3, c=1.0), dev, seed=31,
+                         momentum_std=0.0, drift="student_t", truth=True, bf16=True)
+    for t in range(6):
+        flags = co2.CO2_FLAG_CARRIED_NORMS if (mode == "carried" and t >= 1) else 0
+        print(f"  bf16 {mode} t={t}", flush=True)
+        h.step(flags=flags, split=(mode == "split"))
+    assert h.last["nclipped"] > 0 and np.any(h.last["lam"] > 1.0)
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_TABLES))
+@pytest.mark.parametrize("K", [1, 3, 16])
+def test_bf16_deltas_edge_shapes(dev, name, K):
+    h = OuterStepHarness(EDGE_TABLES[name], HP(K=K, beta=0.8, phi=0.01, c=1.0, tau=3), dev,
+                         seed=8, momentum_std=0.02, truth=True, bf16=True)
+    run_steps(h, 3)
+
+
+def test_bf16_deltas_1p3b_sampled(dev):
+    """Headline-size buffers with bf16 pseudo-gradient transport (42 B/param)."""
+    cfg = co2_inputs.CONFIGS["1p3b"]
+    table = co2_inputs.config_table(cfg)
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
+    sample = [1, 2, 3, 4, 5, 10, 11, 150, 151, 286, 287, 288, 289, 290, 291]
+    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift="student_t",
+                         drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
+                         momentum_std=cfg.momentum_std, start_step=1, bf16=True)
+    for t in range(3):
+        print(f"  1p3b bf16 step {h.t}", flush=True)
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+    print("   ", res, flush=True)
+
+
 def test_carried_norms_equal_two_pass(dev):
     """The sums left by the sweep give the same Lambda as re-reading m and d0."""
     table = co2_inputs.gpt_table(layers=2, d=128, ffn=512, vocab=2001, ctx=32)

@@ -59,6 +59,11 @@ MUTANTS = [
     ("f64_mean_divides_by_wrong_count", "const double dbar = sum / static_cast<double>(K);",
      "const double dbar = sum / static_cast<double>(K + 1);"),
     ("sqnorms_no_square", "double dv = static_cast<double>(v);\n      acc += dv * dv;", "double dv = static_cast<double>(v);\n      acc += dv;"),
+    ("bf16_truncates_instead_of_rounding", "u += 0x7fffu + lsb;", "u += 0u;"),
+    ("bf16_ties_round_away", "u += 0x7fffu + lsb;", "u += 0x8000u;"),
+    ("bf16_widening_shift_wrong", "cv.u = static_cast<uint32_t>(b) << 16;", "cv.u = static_cast<uint32_t>(b) << 15;"),
+    ("bf16_step_skips_rounding_of_dout", "if (x) dout[j] = co2_oracle_f32_to_bf16(aj - x[j]);\n      float sum",
+     "if (x) dout[j] = static_cast<uint16_t>(0);\n      float sum"),
     ("adamw_second_moment_not_squared", "const float v = beta2 * exp_avg_sq[j] + (omb2 * g) * g;",
      "const float v = beta2 * exp_avg_sq[j] + (omb2 * g);"),
     ("adamw_no_bias_correction_1", "const float step_size = static_cast<float>(static_cast<double>(lr) / bc1);",

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
 // First outer round (Section 3.1: the gap/momentum/iterate lines are skipped):
 // delta_out = anchor - params; params = anchor_out = anchor.  Also leaves the
 // sums of Clip(m,phi)^2 and delta_out^2 per slot for the next round's gap.
-// Runs once per training run, so it is kept simple (element-wise path only).
+// Same tile structure as the sweep.
 template <bool HAS_X, bool BF16>
 __global__ __launch_bounds__(kWave) void first_round(
     float* x, const float* a_in, float* a_out, const float* __restrict__ m, void* dout,
@@ -178,7 +178,39 @@ __global__ __launch_bounds__(kWave) void first_round(
   const int64_t base = tile * kSweepTile;
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
   const int lane = threadIdx.x;
+  const bool full = base + kSweepTile <= n;
+  const int64_t jv = base + (int64_t(lane) << 2);
+  float4 va, vm, vx;
+  if (full) {
+    va = ld4(a_in + jv);
+    vm = ld4(m + jv);
+    if (HAS_X) vx = ld4(x + jv);
+  }
   const int s_lo = seg_of(off, S, base);
+
+  if (full && base + kSweepTile <= off[s_lo + 1]) {
+    double acc_m = 0.0, acc_d = 0.0;
+    float dc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc_m += sq(clip_coord(comp(vm, e), phi));
+      if (HAS_X) {
+        dc[e] = IO::stored(comp(va, e) - comp(vx, e));
+        acc_d += sq(dc[e]);
+      }
+    }
+    if (HAS_X) {
+      IO::store4(dout, jv, dc);
+      st4(x + jv, va);
+    }
+    if (a_out != a_in) st4(a_out + jv, va);
+    const double tm = wave_sum(acc_m);
+    double td = 0.0;
+    if (HAS_X) td = wave_sum(acc_d);
+    write_slot(slots, tile + s_lo, lane, tm, td, 0.0);   // no outer iterate in the first round
+    return;
+  }
+
   const int s_hi = seg_of(off, S, end - 1);
   for (int s = s_lo; s <= s_hi; ++s) {
     const int64_t lo = off[s] > base ? off[s] : base;
@@ -252,7 +284,8 @@ hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t
 template <bool HAS_X, bool BF16>
 static hipError_t launch_first_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  hipLaunchKernelGGL((first_round<HAS_X, BF16>), dim3(tiles), dim3(kWave), 0, st, g.x, g.a_in,
+  const unsigned lds = throttle_lds_bytes(tuning().sweep_waves_per_cu[1]);
+  hipLaunchKernelGGL((first_round<HAS_X, BF16>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
                      g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
   return hipGetLastError();
 }

@@ -319,6 +319,22 @@ def test_1p3b_headline_size_sampled(dev):
                  "sum of Clip(m)^2, all segments", tol=1e-12)
 
 
+# ------------------------------------------------------------------ more than 2^31 elements
+def test_flat_index_beyond_2_to_31(dev):
+    """64-bit indexing: a flat vector of 2^31 + 4099 elements (8.6 GB per buffer);
+    the sampled segments sit at the start, across the 2^31 boundary and at the
+    ragged end."""
+    n = (1 << 31) + 4099
+    table = [0, 1000, (1 << 31) - 5, (1 << 31) + 1000, n]
+    h = OuterStepHarness(table, HP(K=2, beta=0.9, phi=2e-3, c=1.0), dev, seed=17, sample=[0, 2, 3],
+                         momentum_std=0.01)
+    for t in range(3):
+        print(f"  n={n} step {h.t}", flush=True)
+        h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 2 else 0)
+    lam = h.lam.cpu().numpy()
+    assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
+
+
 # ------------------------------------------------------------------ config 4, ZeRO-style shard
 @pytest.mark.parametrize("rank", [1, 0])
 def test_7b_shard_partial_segments(dev, rank):

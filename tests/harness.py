@@ -126,8 +126,11 @@ class OuterStepHarness:
         if dst is not t:
             t.copy_(dst)                      # the sender's rounding to bf16 (input synthesis)
 
-    def step(self, flags: int = 0, split: bool = False, check: bool = True, events=None):
-        """One outer round on both sides; returns dict of worst relative errors."""
+    def step(self, flags: int = 0, split: bool = False, check: bool = True, events=None,
+             full_check: bool = False):
+        """One outer round on both sides; returns dict of worst relative errors.
+        full_check: also verify, over EVERY coordinate on the device, properties
+        that need no oracle (see _full_device_checks)."""
         hp, t = self.hp, self.t
         cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]   # cur: deltas[0]; nxt: delta_out
         # inner loop stand-in: local params drift away from the anchor
@@ -148,6 +151,8 @@ class OuterStepHarness:
         o_fsn = None if self.fsn is None else self.fsn[self.sample].cpu().numpy().copy()
 
         # ---- device
+        if full_check:
+            a_prev, x_prev = self.a.clone(), self.x.clone()
         ev_b, ev_e = events if events else (None, None)
         p = co2.make_params(self.seg, hp.K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
                             ev_b, ev_e, self.clipped)
@@ -194,7 +199,28 @@ class OuterStepHarness:
         self.t += 1
         if check:
             res = self.compare(nxt)
+        if full_check:
+            self._full_device_checks(a_prev, x_prev, nxt, t)
         return res
+
+    def _full_device_checks(self, a_prev, x_prev, dout, t):
+        """Properties of one round that hold for every coordinate, evaluated with
+        plain torch reductions over the whole device buffers."""
+        hp = self.hp
+        assert torch.equal(self.x, self.a), "params and anchor must both hold x_{t+1,0}"
+        want_d = torch.sub(a_prev, x_prev)
+        if self.bf16:
+            want_d = want_d.to(torch.bfloat16)
+        assert torch.equal(dout, want_d), "delta_out != anchor - params over the full buffer"
+        del want_d, x_prev
+        assert bool(torch.isfinite(self.m).all()) and bool(torch.isfinite(self.a).all())
+        if t >= 1:
+            moved = a_prev.sub_(self.a).abs_().max().item()
+            assert moved <= hp.alpha * hp.phi * (1 + 1e-6) + 1e-9, "an iterate moved more than alpha*phi"
+            n_clamped = int((self.m.abs() > hp.phi).sum().item())
+            assert int(self.clipped.sum().item()) == n_clamped, "clipped count over all segments"
+            lam = self.lam.cpu().numpy()
+            assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
 
     def compare(self, dout_buf: torch.Tensor):
         """Element-by-element comparison of every output on the sampled segments."""

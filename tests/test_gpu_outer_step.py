@@ -301,7 +301,7 @@ def test_1p3b_headline_size_sampled(dev):
     for t in range(4):
         flags = co2.CO2_FLAG_CARRIED_NORMS if t >= 2 else 0
         print(f"  1p3b step {h.t} flags={flags}", flush=True)
-        res = h.step(flags=flags)
+        res = h.step(flags=flags, full_check=(t == 3))
         print("   ", res, "nclipped(sample)=", h.last["nclipped"], flush=True)
     lam = h.lam.cpu().numpy()
     assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
@@ -314,9 +314,12 @@ def test_1p3b_headline_size_sampled(dev):
     co2.co2_pseudo_grad_norms(p, [own], h.m, out, h.ws)
     got = out.cpu().numpy()
     print("  full-size norms of all segments vs oracle", flush=True)
-    assert_close(got[0], co2_oracle.sqnorms(own.cpu().numpy(), table), "sum of d0^2, all segments", tol=1e-12)
+    # The oracle adds up to 1.3e8 non-negative terms one after the other, so its own sum
+    # is only good to about N * 2^-53 ~ 1e-8 relative (the device's tree order is tighter);
+    # 1e-9 is four orders inside the 1e-5 bar.
+    assert_close(got[0], co2_oracle.sqnorms(own.cpu().numpy(), table), "sum of d0^2, all segments", tol=1e-9)
     assert_close(got[1], co2_oracle.sqnorms(h.m.cpu().numpy(), table, phi=hp.phi),
-                 "sum of Clip(m)^2, all segments", tol=1e-12)
+                 "sum of Clip(m)^2, all segments", tol=1e-9)
 
 
 # ------------------------------------------------------------------ more than 2^31 elements
@@ -348,5 +351,5 @@ def test_7b_shard_partial_segments(dev, rank):
                          drift_scale=cfg.drift_scale, momentum_std=cfg.momentum_std, start_step=1)
     for t in range(3):
         print(f"  7b shard rank {rank} step {h.t}", flush=True)
-        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0, full_check=(t == 2))
     print("7b shard:", res)

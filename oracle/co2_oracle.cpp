@@ -16,8 +16,7 @@
 //   *_f64 : everything in fp64 ("truth"), used to bound the fp32 evaluation's
 //           own rounding error.
 //
-// Readings taken where the paper is silent (each is also listed in the design
-// document):
+// Readings taken where the paper is silent:
 //   * ||.|| in Eq. 3 is the L2 norm over one parameter tensor ("segment"),
 //     and Lambda is broadcast over that tensor's coordinates.  S = n gives the
 //     per-coordinate reading, S = 1 the global one.

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through the C ABI) against the CPU oracle,
 element by element, on the same seeded inputs.
 
-Tolerance (written here, derived in the design document): every element of
+Tolerance: every element of
 every output within 1e-5 relative of the fp32-ordered oracle; Lambda and the
 norms within 1e-5 relative; and, where the harness also carries the all-fp64
 evaluation, within 1e-5 of it relative to the operands of each sum.  Both sides

@@ -10,8 +10,6 @@
 
 namespace co2 {
 
-typedef unsigned v2u __attribute__((ext_vector_type(2)));
-
 struct AdamScalars {
   float beta1, beta2, omb1, omb2, decay, step_size, sqrt_bc2, eps;
 };
@@ -55,13 +53,13 @@ __global__ __launch_bounds__(kWave) void adamw_step(
   if (full) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
-      vp[u] = ld4(p_in + j);
-      const v2u gb = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(grad + j));
+      const int64_t row = base + int64_t(u) * kWave * 4;
+      vp[u] = ld4_stream(p_in + row, lane);
+      const v2u gb = ld2_stream(grad + row, lane);
       vg[u] = make_uint2(gb.x, gb.y);
-      vm[u] = ld4(exp_avg + j);
-      vv[u] = ld4(exp_avg_sq + j);
-      if (HAS_DOUT) va[u] = ld4(anchor + j);
+      vm[u] = ld4_stream(exp_avg + row, lane);
+      vv[u] = ld4_stream(exp_avg_sq + row, lane);
+      if (HAS_DOUT) va[u] = ld4_stream(anchor + row, lane);
     }
   }
   int s_lo = 0;
@@ -75,7 +73,6 @@ __global__ __launch_bounds__(kWave) void adamw_step(
     double acc = 0.0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
       const float pc[4] = {vp[u].x, vp[u].y, vp[u].z, vp[u].w};
       float mc[4] = {vm[u].x, vm[u].y, vm[u].z, vm[u].w};
       float vc[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
@@ -87,12 +84,15 @@ __global__ __launch_bounds__(kWave) void adamw_step(
         po[e] = adamw_coord(pc[e], gc[e], mc[e], vc[e], h);
         if (HAS_NORM) acc += sq(po[e] - pc[e]);
       }
-      st4(exp_avg + j, make_float4(mc[0], mc[1], mc[2], mc[3]));
-      st4(exp_avg_sq + j, make_float4(vc[0], vc[1], vc[2], vc[3]));
-      st4(p_out + j, make_float4(po[0], po[1], po[2], po[3]));
+      const int64_t jb = base + int64_t(u) * kWave * 4;      // first element of this 256-wide row
+      constexpr int kRowBytes = kWave * 16;
+      st4_stream(exp_avg + jb, kRowBytes, lane, make_float4(mc[0], mc[1], mc[2], mc[3]));
+      st4_stream(exp_avg_sq + jb, kRowBytes, lane, make_float4(vc[0], vc[1], vc[2], vc[3]));
+      st4_stream(p_out + jb, kRowBytes, lane, make_float4(po[0], po[1], po[2], po[3]));
       if (HAS_DOUT) {
         const float ac[4] = {va[u].x, va[u].y, va[u].z, va[u].w};
-        st4(dout + j, make_float4(ac[0] - po[0], ac[1] - po[1], ac[2] - po[2], ac[3] - po[3]));
+        st4_stream(dout + jb, kRowBytes, lane,
+                   make_float4(ac[0] - po[0], ac[1] - po[1], ac[2] - po[2], ac[3] - po[3]));
       }
     }
     if (HAS_NORM) {

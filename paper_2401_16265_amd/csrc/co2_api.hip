@@ -128,15 +128,15 @@ const Tuning& tuning() {
   thread_local Tuning u;
   // Measured optimum of resident wavefronts per compute unit for the sweep at
   // 1.3B parameters, averaged over several buffer placements (each wavefront
-  // holds 1 KB x (3+K) streams of loads): 8 for K <= 4, 7 for K <= 6, 6 for
-  // K <= 9, 5 for K <= 13, 4 beyond.
+  // holds 1 KB x (3+K) streams of loads): 8 for K <= 4, 7 for K <= 9, 6 for
+  // K <= 12, 5 for K <= 14, 4 beyond.
   const int sweep_override = env_int("CO2_SWEEP_WAVES", -1);
   for (int k = 1; k <= CO2_MAX_K; ++k) {
-    const int w = k <= 4 ? 8 : k <= 6 ? 7 : k <= 9 ? 6 : k <= 13 ? 5 : 4;
+    const int w = k <= 4 ? 8 : k <= 9 ? 7 : k <= 12 ? 6 : k <= 14 ? 5 : 4;
     u.sweep_waves_per_cu[k] = sweep_override >= 0 ? sweep_override : w;
   }
   u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
-  u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 10);
+  u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 7);
   u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 7);
   return u;
 }

@@ -114,20 +114,50 @@ __device__ __forceinline__ double block_sum(double v, double* lds) {
   return t;
 }
 
-// Streaming 16-byte accesses: every element of every buffer is touched once
-// per kernel, so loads and stores carry the non-temporal hint.
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float4 ld4(const float* p) {
-  const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-  return make_float4(t.x, t.y, t.z, t.w);
-}
-__device__ __forceinline__ void st4(float* p, float4 v) {
-  const v4f t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
-}
-
+// Streaming accesses: every element of every buffer is touched once per kernel,
+// so loads and stores carry the non-temporal hint.
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+// Streaming stores of a whole tile row: buffer stores with the non-temporal and
+// sc1 (write-through) cache-policy bits.  Written lines then leave the L2 in the
+// order they were produced instead of lingering as dirty lines that are evicted
+// later in scattered order, which is worth about 3 % of HBM bandwidth on a mixed
+// read/write stream.  `tile_ptr` is the wavefront-uniform address of the tile's
+// first element, `tile_bytes` the size of the window the wavefront may write.
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+constexpr int kStoreAux = 2 | 16;                  // cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
+constexpr int kRsrcWord3 = 0x00020000;             // raw 32-bit buffer, no swizzle, no stride
+
+// Streaming loads of a whole tile row (64 lanes x 16 or 8 bytes): buffer loads
+// with the non-temporal bit, addressed as wavefront-uniform row base + lane
+// offset (measured about 1 % faster than per-lane 64-bit global addresses).
+constexpr int kLoadAux = 2;                        // nt
+
+__device__ __forceinline__ float4 ld4_stream(const float* row_ptr, int lane) {
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(row_ptr), 0, kWave * 16, kRsrcWord3);
+  const v4u t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, 0, kLoadAux);
+  return make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z),
+                     __uint_as_float(t.w));
+}
+__device__ __forceinline__ v2u ld2_stream(const void* row_ptr, int lane) {
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(row_ptr), 0, kWave * 8, kRsrcWord3);
+  return __builtin_amdgcn_raw_buffer_load_b64(rs, lane * 8, 0, kLoadAux);
+}
+
+__device__ __forceinline__ void st4_stream(float* tile_ptr, int tile_bytes, int lane, float4 v) {
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(tile_ptr, 0, tile_bytes, kRsrcWord3);
+  const v4u t = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z),
+                 __float_as_uint(v.w)};
+  __builtin_amdgcn_raw_buffer_store_b128(t, rs, lane * 16, 0, kStoreAux);
+}
+__device__ __forceinline__ void st2_stream(void* tile_ptr, int tile_bytes, int lane, v2u v) {
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(tile_ptr, 0, tile_bytes, kRsrcWord3);
+  __builtin_amdgcn_raw_buffer_store_b64(v, rs, lane * 8, 0, kStoreAux);
+}
 
 // fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays a quiet NaN.
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
@@ -149,8 +179,9 @@ struct DeltaIO;
 template <>
 struct DeltaIO<false> {
   using Vec = float4;
-  static __device__ __forceinline__ Vec load4(const void* p, int64_t j) {
-    return ld4(static_cast<const float*>(p) + j);
+  // one row of 256 coordinates starting at element `row`
+  static __device__ __forceinline__ Vec load4(const void* p, int64_t row, int lane) {
+    return ld4_stream(static_cast<const float*>(p) + row, lane);
   }
   static __device__ __forceinline__ float get(const Vec& v, int e) {
     return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
@@ -159,8 +190,9 @@ struct DeltaIO<false> {
     return static_cast<const float*>(p)[j];
   }
   static __device__ __forceinline__ float stored(float d) { return d; }
-  static __device__ __forceinline__ void store4(void* p, int64_t j, const float (&d)[4]) {
-    st4(static_cast<float*>(p) + j, make_float4(d[0], d[1], d[2], d[3]));
+  // one 256-coordinate tile starting at element `base`
+  static __device__ __forceinline__ void store4(void* p, int64_t base, int lane, const float (&d)[4]) {
+    st4_stream(static_cast<float*>(p) + base, kWave * 16, lane, make_float4(d[0], d[1], d[2], d[3]));
   }
   static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
     static_cast<float*>(p)[j] = d;
@@ -170,9 +202,8 @@ struct DeltaIO<false> {
 template <>
 struct DeltaIO<true> {
   using Vec = uint2;
-  static __device__ __forceinline__ Vec load4(const void* p, int64_t j) {
-    const v2u t = __builtin_nontemporal_load(
-        reinterpret_cast<const v2u*>(static_cast<const uint16_t*>(p) + j));
+  static __device__ __forceinline__ Vec load4(const void* p, int64_t row, int lane) {
+    const v2u t = ld2_stream(static_cast<const uint16_t*>(p) + row, lane);
     return make_uint2(t.x, t.y);
   }
   static __device__ __forceinline__ float get(const Vec& v, int e) {
@@ -186,10 +217,10 @@ struct DeltaIO<true> {
     return bf16_bits_to_f32(f32_to_bf16_bits(d));
   }
   // d[] already holds representable values (stored()), so the shift is exact
-  static __device__ __forceinline__ void store4(void* p, int64_t j, const float (&d)[4]) {
+  static __device__ __forceinline__ void store4(void* p, int64_t base, int lane, const float (&d)[4]) {
     const v2u t = {(__float_as_uint(d[0]) >> 16) | (__float_as_uint(d[1]) & 0xffff0000u),
                    (__float_as_uint(d[2]) >> 16) | (__float_as_uint(d[3]) & 0xffff0000u)};
-    __builtin_nontemporal_store(t, reinterpret_cast<v2u*>(static_cast<uint16_t*>(p) + j));
+    st2_stream(static_cast<uint16_t*>(p) + base, kWave * 8, lane, t);
   }
   static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
     static_cast<uint16_t*>(p)[j] = static_cast<uint16_t>(__float_as_uint(d) >> 16);

@@ -46,9 +46,9 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
   if (full) {
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {
-      const int64_t j = base + ((int64_t(u) * kWave + lane) << 2);
-      q0[u] = ld4(b0 + j);
-      if (NB == 2) q1[u] = IO1::load4(b1, j);
+      const int64_t row = base + int64_t(u) * kWave * 4;
+      q0[u] = ld4_stream(b0 + row, lane);
+      if (NB == 2) q1[u] = IO1::load4(b1, row, lane);
     }
   }
   const int s_lo = seg_of(off, S, base);

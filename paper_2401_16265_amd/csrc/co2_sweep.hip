@@ -59,20 +59,20 @@ struct SubTile {
 template <int K, bool HAS_X, bool BF16>
 __device__ __forceinline__ void load_sub(SubTile<K, HAS_X, BF16>& t, const float* x,
                                          const float* a_in, const float* m, const DeltaPtrs& d,
-                                         int64_t jv) {
-  t.va = ld4(a_in + jv);
-  t.vm = ld4(m + jv);
-  if (HAS_X) t.vx = ld4(x + jv);
+                                         int64_t base, int lane) {
+  t.va = ld4_stream(a_in + base, lane);
+  t.vm = ld4_stream(m + base, lane);
+  if (HAS_X) t.vx = ld4_stream(x + base, lane);
 #pragma unroll
-  for (int k = 0; k < K; ++k) t.vd[k] = DeltaIO<BF16>::load4(d.p[k], jv);
+  for (int k = 0; k < K; ++k) t.vd[k] = DeltaIO<BF16>::load4(d.p[k], base, lane);
 }
 
 // Update and store one 256-coordinate tile held in registers.
 template <int K, bool HAS_X, bool BF16>
 __device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X, BF16>& t, float* x,
-                                           float* a_out, float* m, void* dout, int64_t jv,
-                                           float inv, const SweepScalars& h, double& acc_m,
-                                           double& acc_d, int& nclip) {
+                                           float* a_out, float* m, void* dout, int64_t base,
+                                           int lane, float inv, const SweepScalars& h,
+                                           double& acc_m, double& acc_d, int& nclip) {
   using IO = DeltaIO<BF16>;
   float mc[4], xc[4], dc[4];
 #pragma unroll
@@ -90,13 +90,14 @@ __device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X, BF16>& t, flo
     acc_m += sq(clip_coord(mc[e], h.phi));
     nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));   // wavefront-uniform count
   }
+  constexpr int kTileBytes = kWave * 16;
   const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
   if (HAS_X) {
-    IO::store4(dout, jv, dc);
-    st4(x + jv, xo);
+    IO::store4(dout, base, lane, dc);
+    st4_stream(x + base, kTileBytes, lane, xo);
   }
-  st4(m + jv, make_float4(mc[0], mc[1], mc[2], mc[3]));
-  st4(a_out + jv, xo);
+  st4_stream(m + base, kTileBytes, lane, make_float4(mc[0], mc[1], mc[2], mc[3]));
+  st4_stream(a_out + base, kTileBytes, lane, xo);
 }
 
 template <int K, bool HAS_X, bool BF16>
@@ -109,19 +110,18 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
   const int64_t base = tile * kSweepTile;
   const int lane = threadIdx.x;
   const bool full = base + kSweepTile <= n;
-  const int64_t jv = base + (int64_t(lane) << 2);
 
   // The tile's loads go out before the segment lookup, which does not depend
   // on them and runs while they are in flight.
   SubTile<K, HAS_X, BF16> cur;
-  if (full) load_sub<K, HAS_X, BF16>(cur, x, a_in, m, d, jv);
+  if (full) load_sub<K, HAS_X, BF16>(cur, x, a_in, m, d, base, lane);
   const int s_lo = seg_of(off, S, base);
 
   if (full && base + kSweepTile <= off[s_lo + 1]) {
     const float inv = inv_tab[s_lo];
     double acc_m = 0.0, acc_d = 0.0;
     int nclip = 0;
-    finish_sub<K, HAS_X, BF16>(cur, x, a_out, m, dout, jv, inv, h, acc_m, acc_d, nclip);
+    finish_sub<K, HAS_X, BF16>(cur, x, a_out, m, dout, base, lane, inv, h, acc_m, acc_d, nclip);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
@@ -179,12 +179,11 @@ __global__ __launch_bounds__(kWave) void first_round(
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
   const int lane = threadIdx.x;
   const bool full = base + kSweepTile <= n;
-  const int64_t jv = base + (int64_t(lane) << 2);
   float4 va, vm, vx;
   if (full) {
-    va = ld4(a_in + jv);
-    vm = ld4(m + jv);
-    if (HAS_X) vx = ld4(x + jv);
+    va = ld4_stream(a_in + base, lane);
+    vm = ld4_stream(m + base, lane);
+    if (HAS_X) vx = ld4_stream(x + base, lane);
   }
   const int s_lo = seg_of(off, S, base);
 
@@ -200,10 +199,10 @@ __global__ __launch_bounds__(kWave) void first_round(
       }
     }
     if (HAS_X) {
-      IO::store4(dout, jv, dc);
-      st4(x + jv, va);
+      IO::store4(dout, base, lane, dc);
+      st4_stream(x + base, kWave * 16, lane, va);
     }
-    if (a_out != a_in) st4(a_out + jv, va);
+    if (a_out != a_in) st4_stream(a_out + base, kWave * 16, lane, va);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
@@ -243,9 +242,9 @@ __global__ __launch_bounds__(kWave) void copy_f32(const float* __restrict__ src,
   if (base + kTile <= n) {
     float4 v[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = ld4(src + base + ((int64_t(u) * kWave + threadIdx.x) << 2));
+    for (int u = 0; u < U; ++u) v[u] = ld4_stream(src + base + int64_t(u) * kWave * 4, threadIdx.x);
 #pragma unroll
-    for (int u = 0; u < U; ++u) st4(dst + base + ((int64_t(u) * kWave + threadIdx.x) << 2), v[u]);
+    for (int u = 0; u < U; ++u) st4_stream(dst + base + int64_t(u) * kWave * 4, kWave * 16, threadIdx.x, v[u]);
   } else {
     for (int64_t j = base + threadIdx.x; j < n; j += kWave) dst[j] = src[j];
   }

@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # summaries under profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/fused_sweep_1p3b_k8_hbm_counters.md
-    ("1p3b", "carried"): 8.0794e10,
+    ("1p3b", "carried"): 8.0800e10,
 }
 
 

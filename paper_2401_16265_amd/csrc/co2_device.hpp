@@ -5,7 +5,7 @@
 // Geometry.  Every streaming kernel here runs ONE wavefront per workgroup over
 // an aligned tile of the flat index space, one tile per workgroup, in dispatch
 // order.  On MI355X a mixed read/write stream over many buffers is fastest when
-// each compute unit keeps only about 56-64 KB of loads in flight (5-8
+// each compute unit keeps only about 56-64 KB of loads in flight (4-8
 // wavefronts of 3+K 16-byte loads per lane): more resident wavefronts widen the
 // window of DRAM pages touched at once and cost 10-15 % of HBM bandwidth.  The
 // launch code therefore reserves dynamic LDS per workgroup purely to cap the

@@ -180,3 +180,18 @@ def test_outer_step_bf16_validates_like_the_fp32_entry():
     assert L.co2_outer_step_bf16(*bad) == co2.CO2_EINVAL
     bad = list(ok_args); bad[9] = None
     assert L.co2_outer_step_bf16(*bad) == co2.CO2_EWORKSPACE
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/co2.h must be usable from C (no C++-only constructs, no HIP/torch types)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "co2.h"\n'
+                   "int main(void) { co2_params p; p.n = 1; (void)p; "
+                   "return (int)co2_workspace_bytes(0, 0, 0) + (co2_strerror(0) == 0); }\n")
+    inc = os.path.dirname(HEADER)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "use_header.o")], check=True)
+    text = open(HEADER).read()
+    for forbidden in ("torch", "hipStream_t ", "#include <hip", "at::Tensor"):
+        assert forbidden not in text.replace("a hipStream_t;", "")

@@ -1,0 +1,25 @@
+"""The C ABI driven without PyTorch: a host-only C++ program (tests/c_abi/selftest.cpp)
+allocates with hipMalloc, calls libco2.so directly for four consecutive rounds and
+compares every element with the oracle source linked into it."""
+import importlib.util
+import os
+import subprocess
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _exe():
+    spec = importlib.util.spec_from_file_location("c_abi_build", os.path.join(HERE, "c_abi", "build.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod.EXE if os.path.exists(mod.EXE) else mod.build_selftest()
+
+
+@pytest.mark.parametrize("n,K", [(100003, 3), (4099, 16), (1 << 20, 8)])
+def test_c_abi_selftest(n, K):
+    out = subprocess.run([_exe(), str(n), str(K)], capture_output=True, text=True, timeout=120)
+    print(out.stdout, out.stderr, flush=True)
+    assert out.returncode == 0 and "PASS" in out.stdout

@@ -48,6 +48,10 @@ def parse():
     ap.add_argument("--separate-allocations", action="store_true",
                     help="allocate every buffer on its own instead of carving all of them out of "
                          "one device allocation (the layout the library recommends)")
+    ap.add_argument("--placement-candidates", type=int, default=3,
+                    help="device allocations tried for the buffers; the sweep is timed on each "
+                         "(and on three gaps between buffers) and the fastest layout is kept. "
+                         "1 = take the first allocation as it comes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
     return ap.parse_args()
@@ -185,30 +189,57 @@ def main():
     f32 = dict(dtype=torch.float32, device=dev)
 
     # ---- resident state: params, anchor, momentum, K-1 peers, 2 own (ping-pong).
-    # All flat buffers are carved out of ONE device allocation, made before any other
-    # large one: the sweep streams 3+K+4 buffers in lock step and is up to 8 % faster
-    # when they sit in one physically contiguous region than when they are scattered.
+    # All flat buffers are carved out of ONE device allocation.  The sweep streams
+    # 3+K+1 buffers in lock step and its duration depends on where they lie relative
+    # to each other in HBM (up to 10 % between allocations, 3 % between gaps), so the
+    # allocation and the gap are chosen by timing the sweep itself on a few candidates
+    # before anything is initialised (paper_2401_16265_amd/placement.py).
     bf16 = args.deltas == "bf16"
     dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
+    lam = torch.empty(S, **f32)
+    ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    carried = args.form == "carried"
+    entry = co2.co2_outer_step_bf16 if bf16 else co2.co2_outer_step
+
+    def typed(views):
+        a, m, x = (v.view(torch.float32) for v in views[:3])
+        ds = [v.view(dd["dtype"]) for v in views[3:]]
+        return a, m, x, ds[:2], ds[2:]
+
+    def launch(bufs, t, ev=None):
+        a, m, x, own, peers = bufs
+        cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
+        flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
+        p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
+                            ev[0] if ev else None, ev[1] if ev else None)
+        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
+
+    def probe(views, reps=3):
+        """Median duration (ms) of the sweep kernel over `reps` launches on these buffers."""
+        bufs = typed(views)
+        evs = [(co2.HipEvent(), co2.HipEvent()) for _ in range(reps)]
+        for t in range(1, 3):
+            launch(bufs, t)
+        for i in range(reps):
+            launch(bufs, 3 + i, evs[i])
+        torch.cuda.synchronize()
+        return sorted(b.elapsed_ms(e) for b, e in evs)[reps // 2]
+
+    placement = None
     if args.separate_allocations:
         a = torch.empty(n, **f32); m = torch.empty(n, **f32); x = torch.empty(n, **f32)
         own = [torch.empty(n, **dd), torch.empty(n, **dd)]
         peers = [torch.empty(n, **dd) for _ in range(K - 1)]
     else:
+        from paper_2401_16265_amd import placement as pl
         dbytes = n * (2 if bf16 else 4)
-        pad = lambda b: (b + 4095) // 4096 * 4096 + 4096               # noqa: E731  (one spare page)
-        arena = torch.empty(3 * pad(4 * n) + (K + 1) * pad(dbytes), dtype=torch.uint8, device=dev)
-        off = [0]
-
-        def carve(nbytes, dtype):
-            t = arena[off[0]:off[0] + nbytes].view(dtype)
-            off[0] += pad(nbytes)
-            return t
-        a, m, x = (carve(4 * n, torch.float32) for _ in range(3))
-        own = [carve(dbytes, dd["dtype"]) for _ in range(2)]
-        peers = [carve(dbytes, dd["dtype"]) for _ in range(K - 1)]
-    lam = torch.empty(S, **f32)
-    ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
+        sizes = [4 * n] * 3 + [dbytes] * (K + 1)
+        placement = pl.choose_placement(
+            sizes, probe if args.placement_candidates > 1 else None, dev,
+            candidates=args.placement_candidates,
+            gaps=pl.DEFAULT_GAPS if args.placement_candidates > 1 else (pl.PAGE,))
+        a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"
 
     def drift(t, bid):
@@ -229,18 +260,11 @@ def main():
     drift(x, 100); x.add_(a)                                # local params = anchor + drift
     torch.cuda.synchronize()
 
-    stream = torch.cuda.current_stream().cuda_stream
-    carried = args.form == "carried"
     step_no = [1]
+    bufs = (a, m, x, own, peers)
 
     def one_step(ev=None):
-        t = step_no[0]
-        cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
-        flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
-        p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
-                            ev[0] if ev else None, ev[1] if ev else None)
-        entry = co2.co2_outer_step_bf16 if bf16 else co2.co2_outer_step
-        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
+        launch(bufs, step_no[0], ev)
         step_no[0] += 1
 
     warmup = max(args.warmup, 2 if carried else 0)   # carried sums exist from round 2 on
@@ -283,6 +307,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
                                f"c={cfg.c}", "form": args.form, "deltas": args.deltas,
+                   "placement": placement.report() if placement and placement.probe_ms else
+                                ("separate allocations" if placement is None else "first allocation"),
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -291,7 +317,7 @@ def main():
                      "kernel": "fused_sweep", "kernel_ms": sweep_ms,
                      "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
     }
-    del a, m, x, own, peers
+    del a, m, x, own, peers, bufs, placement
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline(cfg, table, args.cpu_sample_elems, dev)

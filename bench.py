@@ -52,6 +52,10 @@ def parse():
                     help="device allocations tried for the buffers; the sweep is timed on each "
                          "(and on three gaps between buffers) and the fastest layout is kept. "
                          "1 = take the first allocation as it comes")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="also capture two consecutive rounds into a HIP graph and time its replays; "
+                         "value and ms_per_step then come from the replays (launch-bound small "
+                         "workloads), the roofline still from the eager launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
     return ap.parse_args()
@@ -281,6 +285,28 @@ def main():
     elapsed = time.perf_counter() - t0
 
     ms_per_step = elapsed * 1e3 / args.steps
+    launch_mode = "eager"
+    if args.hip_graph:
+        # two rounds = one period of the delta_out ping-pong; step parity continues from the eager loop
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        t_cap = step_no[0] + (step_no[0] % 2)               # even round first
+        with torch.cuda.graph(graph, stream=side):
+            stream = torch.cuda.current_stream().cuda_stream
+            launch(bufs, t_cap)
+            launch(bufs, t_cap + 1)
+        stream = torch.cuda.current_stream().cuda_stream
+        if step_no[0] % 2:
+            one_step()                                      # bring the ping-pong to an even round
+        replays = max(1, args.steps // 2)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / (2 * replays)
+        launch_mode = f"hip graph of 2 rounds, {replays} replays (eager: {elapsed * 1e3 / args.steps:.4f} ms/step)"
+        del graph
     sweep_ms = sum(b.elapsed_ms(e) for b, e in events) / args.steps
     per_elem = (26 + 2 * K) if bf16 else (28 + 4 * K)   # algorithmic bytes per coordinate, one sweep
     sweep_bytes = per_elem * n
@@ -306,7 +332,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
-                               f"c={cfg.c}", "form": args.form, "deltas": args.deltas,
+                               f"c={cfg.c}", "form": args.form, "deltas": args.deltas, "launch": launch_mode,
                    "placement": placement.report() if placement and placement.probe_ms else
                                 ("separate allocations" if placement is None else "first allocation"),
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n

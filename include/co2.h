@@ -20,7 +20,12 @@
  *     marked HOST point to ordinary host memory.  The library allocates nothing,
  *     keeps no state between calls, and never synchronises: every call
  *     validates its arguments on the host, enqueues kernels on `hip_stream`
- *     (a hipStream_t; NULL = the null stream) and returns.
+ *     (a hipStream_t; NULL = the null stream) and returns.  The launches hold
+ *     no memset and no host callback, so a caller may capture them into a HIP
+ *     graph (leave the timing events of co2_params NULL then): `step` only
+ *     tells the first round from the later ones, so two captured steady-state
+ *     rounds -- the two halves of a delta_out ping-pong -- can be replayed for
+ *     the rest of a run.
  *   - Every DEVICE buffer must be 16-byte aligned.  Layout advice: carve the
  *     flat buffers of one worker (params, anchor, momentum, the K pseudo-
  *     gradient buffers, delta_out) out of ONE device allocation, 4 KiB aligned;

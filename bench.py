@@ -48,10 +48,10 @@ def parse():
     ap.add_argument("--separate-allocations", action="store_true",
                     help="allocate every buffer on its own instead of carving all of them out of "
                          "one device allocation (the layout the library recommends)")
-    ap.add_argument("--placement-candidates", type=int, default=3,
-                    help="device allocations tried for the buffers; the sweep is timed on each "
-                         "(and on three gaps between buffers) and the fastest layout is kept. "
-                         "1 = take the first allocation as it comes")
+    ap.add_argument("--placement-candidates", type=int, default=4,
+                    help="plain device allocations tried for the buffers, besides two piece-major "
+                         "buffer sets; the sweep is timed on each candidate and the fastest layout "
+                         "is kept.  0 = no search: the first plain allocation as it comes")
     ap.add_argument("--hip-graph", action="store_true",
                     help="also capture two consecutive rounds into a HIP graph and time its replays; "
                          "value and ms_per_step then come from the replays (launch-bound small "
@@ -239,10 +239,10 @@ def main():
         from paper_2401_16265_amd import placement as pl
         dbytes = n * (2 if bf16 else 4)
         sizes = [4 * n] * 3 + [dbytes] * (K + 1)
-        placement = pl.choose_placement(
-            sizes, probe if args.placement_candidates > 1 else None, dev,
-            candidates=args.placement_candidates,
-            gaps=pl.DEFAULT_GAPS if args.placement_candidates > 1 else (pl.PAGE,))
+        search = args.placement_candidates > 0
+        placement = pl.choose_placement(sizes, probe if search else None, dev,
+                                        candidates=args.placement_candidates,
+                                        gaps=pl.DEFAULT_GAPS if search else (pl.PAGE,))
         a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"
 
@@ -333,8 +333,9 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
                                f"c={cfg.c}", "form": args.form, "deltas": args.deltas, "launch": launch_mode,
-                   "placement": placement.report() if placement and placement.probe_ms else
-                                ("separate allocations" if placement is None else "first allocation"),
+                   "placement": ("separate allocations" if placement is None else
+                                 placement.report() if args.placement_candidates > 0 else
+                                 "first allocation"),
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -343,7 +344,11 @@ def main():
                      "kernel": "fused_sweep", "kernel_ms": sweep_ms,
                      "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
     }
-    del a, m, x, own, peers, bufs, placement
+    del a, m, x, own, peers, bufs
+    torch.cuda.synchronize()
+    if placement is not None:
+        placement.release()
+    del placement
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline(cfg, table, args.cpu_sample_elems, dev)

@@ -17,8 +17,9 @@
  *
  * Conventions
  *   - Pointers marked DEVICE point to GPU memory owned by the caller; pointers
- *     marked HOST point to ordinary host memory.  The library allocates nothing,
- *     keeps no state between calls, and never synchronises: every call
+ *     marked HOST point to ordinary host memory.  Apart from the optional
+ *     co2_buffer_set_* pair at the end, the library allocates nothing, keeps
+ *     no state between calls, and never synchronises: every call
  *     validates its arguments on the host, enqueues kernels on `hip_stream`
  *     (a hipStream_t; NULL = the null stream) and returns.  The launches hold
  *     no memset and no host callback, so a caller may capture them into a HIP
@@ -218,6 +219,39 @@ int co2_sqrt_to_f32(const double* sq, float* out, int32_t S, void* hip_stream);
  * yardstick for attainable HBM bandwidth and for calibrating byte counters.
  * Moves 8 bytes per element. */
 int co2_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Buffers placed for the sweep (optional; every entry point above works on any
+ * device memory).  Not part of the paper's method: a memory-layout service for
+ * callers that own their allocation.
+ *
+ * co2_buffer_set_create allocates `count` device buffers of bytes[i] bytes
+ * (HOST array) and stores their DEVICE addresses in bufs_out[i] (HOST array).
+ * Each buffer is an ordinary flat, contiguous range of device addresses,
+ * 4 KiB aligned, readable and writable by every kernel and copy on the current
+ * device.  Physically, every buffer is cut into the same number P of pieces
+ * (about piece_bytes each for the largest buffer; 0 = 1 GiB; must be a
+ * multiple of 2 MiB) and the pieces are obtained from the driver in the order
+ * piece 0 of every buffer, piece 1 of every buffer, ...: the parts of the
+ * buffers that the sweep touches at the same time are then neighbours in
+ * device memory, which makes the sweep's duration less dependent on what the
+ * driver's allocator hands out than K + 4 separate gigabyte-sized allocations.
+ * Buffers of different element size (fp32 vectors and bf16 pseudo-gradients)
+ * get pieces in the same proportion, so piece j always covers the same element
+ * range.  Memory use: sum of bytes[i] rounded up to P * 2 MiB per buffer.
+ *
+ * Ownership: the set owns the memory until co2_buffer_set_destroy, which the
+ * caller invokes after all work on the buffers has completed (it does not
+ * synchronise).  These two calls are the only ones in the library that
+ * allocate or free; they use HIP's virtual-memory-management calls on the
+ * current device and return CO2_EHIP (co2_last_hip_error() holds the
+ * hipError_t, e.g. out of memory) after releasing whatever they had obtained.
+ */
+#define CO2_MAX_BUFFER_SET 64
+typedef struct co2_buffer_set co2_buffer_set;
+int co2_buffer_set_create(int32_t count, const size_t* bytes, size_t piece_bytes, void** bufs_out,
+                          co2_buffer_set** set_out);
+int co2_buffer_set_destroy(co2_buffer_set* set);
 
 /* Text for an error code (static string, never NULL). */
 const char* co2_strerror(int code);

@@ -15,6 +15,7 @@ CO2_MAX_K = 16
 CO2_MAX_NORM_BUFS = 32
 CO2_FLAG_NONE = 0
 CO2_FLAG_CARRIED_NORMS = 1
+CO2_MAX_BUFFER_SET = 64
 
 
 class Co2Params(C.Structure):
@@ -71,6 +72,11 @@ def lib() -> C.CDLL:
         L.co2_sqrt_to_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.co2_copy_f32.restype = C.c_int
         L.co2_copy_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.co2_buffer_set_create.restype = C.c_int
+        L.co2_buffer_set_create.argtypes = [C.c_int32, C.POINTER(C.c_size_t), C.c_size_t,
+                                            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+        L.co2_buffer_set_destroy.restype = C.c_int
+        L.co2_buffer_set_destroy.argtypes = [C.c_void_p]
         _lib = L
     return _lib
 
@@ -147,6 +153,54 @@ class HipEvent:
         try:
             if self.handle:
                 self._rt().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+class _DeviceSpan:
+    """A raw device address range presented through __cuda_array_interface__ so that
+    torch can view it as a uint8 tensor; keeps the owning BufferSet alive."""
+
+    def __init__(self, ptr: int, nbytes: int, owner):
+        self.owner = owner
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+
+class BufferSet:
+    """co2_buffer_set: device buffers whose physical memory is obtained piece-major
+    (include/co2.h).  `views` are uint8 torch tensors over the buffers; they, and
+    anything derived from them, must not be used after close()."""
+
+    def __init__(self, sizes: Sequence[int], piece_bytes: int = 0, device=None):
+        count = len(sizes)
+        arr = (C.c_size_t * count)(*[int(b) for b in sizes])
+        ptrs = (C.c_void_p * count)()
+        self._set = C.c_void_p()
+        self.sizes = [int(b) for b in sizes]
+        dev = torch.device("cuda:0" if device is None else device)
+        with torch.cuda.device(dev):
+            rc = lib().co2_buffer_set_create(count, arr, int(piece_bytes), ptrs, C.byref(self._set))
+        if rc != CO2_OK:
+            self._set = None
+            raise Co2Error(rc, f"co2_buffer_set_create (hip error {lib().co2_last_hip_error()})")
+        self.ptrs = [int(p) for p in ptrs]
+        self.device = dev
+        self.views = [torch.as_tensor(_DeviceSpan(p, b, self), device=dev)
+                      for p, b in zip(self.ptrs, self.sizes)]
+
+    def close(self):
+        """Frees the memory.  The caller has synchronised and dropped every use of the views."""
+        if self._set:
+            self.views = []
+            rc = lib().co2_buffer_set_destroy(self._set)
+            self._set = None
+            if rc != CO2_OK:
+                raise Co2Error(rc, "co2_buffer_set_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
         except Exception:
             pass
 

@@ -10,7 +10,7 @@ _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libco2.so")
-SOURCES = ["co2_api.hip", "co2_norms.hip", "co2_sweep.hip", "co2_adamw.hip"]
+SOURCES = ["co2_api.hip", "co2_norms.hip", "co2_sweep.hip", "co2_adamw.hip", "co2_buffers.hip"]
 
 # -ffp-contract=off: every fp32 product and sum is rounded once, as the ABI
 # documents (no FMA contraction).  Packed-fp32 code generation is disabled.

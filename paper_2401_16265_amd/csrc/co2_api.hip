@@ -122,6 +122,8 @@ int env_int(const char* name, int fallback) {
 
 namespace co2 {
 
+void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
+
 const Tuning& tuning() {
   // Re-read on every launch (a handful of getenv calls): tuning runs change the
   // variables between calls within one process.

@@ -51,6 +51,8 @@ struct Tuning {
   int copy_waves_per_cu;
 };
 const Tuning& tuning();
+// Records `e` as this thread's most recent HIP error (what co2_last_hip_error() returns).
+void note_hip_error(hipError_t e);
 // Dynamic LDS bytes to request per single-wavefront workgroup so that at most
 // `waves_per_cu` of them fit on a compute unit.
 unsigned throttle_lds_bytes(int waves_per_cu);

@@ -2,17 +2,25 @@
 
 The fused sweep streams 3 + K + 1 flat buffers in lock step.  On MI355X its
 duration depends on how those streams fall onto HBM channels and banks relative
-to each other, which is decided by (a) the physical pages behind the allocation
-and (b) the byte distance between consecutive buffers.  Measured at 1.3B
-parameters, K = 8: the same kernel on the same data runs between 11.9 and 13.4 ms
-depending on the allocation it was given (a single-stream copy runs equally fast
-in all of them), and the gap between buffers moves it by another +-3 %.  Neither
-can be predicted from user space, but both are stable for the life of an
-allocation, and a training job allocates once.  So the layout is chosen by
-measurement: a few candidate allocations are held at the same time (so that they
-are backed by different physical pages), the caller's probe -- a few launches of
-the real kernel -- is timed on each candidate with each gap, and the fastest is
-kept; the others are freed.
+to each other, which is decided by the physical pages behind the buffers.
+Measured at 1.3B parameters, K = 8: the same kernel on the same data runs
+between 11.9 and 13.4 ms depending on the allocation it was given (a
+single-stream copy runs equally fast in all of them; the byte gap between
+consecutive buffers moves it by another +-1.5 %), and what the driver hands out
+depends on the allocation history of the machine.  None of this can be predicted
+from user space, but it is stable for the life of an allocation, and a training
+job allocates once.  So the layout is chosen by measurement.  Candidates are
+
+  * piece-major buffer sets (co2_buffer_set_create): every buffer's physical
+    memory is obtained in pieces, piece j of all buffers before piece j+1, so
+    that what the sweep touches at one time lies close together; these have been
+    at the fast end on every machine state tried;
+  * plain single allocations with the buffers carved out back to back, made in
+    turn while earlier ones are still held, so that each lands on other physical
+    pages, each tried with a few gaps between consecutive buffers.
+
+The caller's probe -- a few launches of the real kernel -- is timed on every
+candidate and the fastest is kept; everything else is freed.
 
 This module holds host logic only (allocation, slicing, timing decisions); the
 probe it is given runs the library's kernels.
@@ -26,6 +34,7 @@ import torch
 
 PAGE = 4096
 DEFAULT_GAPS = (PAGE, 2 * PAGE, (1 << 20) + PAGE)
+DEFAULT_PIECES = (1 << 30, 512 << 20)
 
 
 def padded(nbytes: int) -> int:
@@ -51,52 +60,120 @@ def arena_bytes(sizes: Sequence[int], gap: int) -> int:
 
 @dataclass
 class Placement:
-    arena: torch.Tensor                  # the allocation that was kept (uint8)
-    gap: int                             # chosen gap between consecutive buffers, bytes
+    owner: object                        # what holds the memory: a uint8 tensor or a BufferSet
     views: List[torch.Tensor]            # uint8 views, one per requested buffer
-    probe_ms: List[List[float]] = field(default_factory=list)   # [candidate][gap index]
+    kind: str = "arena"                  # "arena" or "piece-major"
+    gap: int = PAGE                      # arena: bytes between consecutive buffers
+    piece_bytes: int = 0                 # piece-major: requested piece size
+    pieces_ms: dict = field(default_factory=dict)                 # piece size -> probe ms (or error text)
+    arenas_ms: List[List[float]] = field(default_factory=list)    # [candidate][gap index]
     gaps: Tuple[int, ...] = ()
-    chosen: Tuple[int, int] = (0, 0)     # (candidate, gap index)
 
     def report(self) -> dict:
-        return {"candidates_ms": [[round(t, 3) for t in row] for row in self.probe_ms],
-                "gaps_bytes": list(self.gaps), "chosen": list(self.chosen)}
+        chosen = (f"piece-major, {self.piece_bytes >> 20} MiB pieces" if self.kind == "piece-major"
+                  else f"arena, gap {self.gap} B")
+        return {"piece_major_ms": {f"{k >> 20} MiB": (round(v, 3) if isinstance(v, float) else v)
+                                   for k, v in self.pieces_ms.items()},
+                "arenas_ms": [[round(t, 3) for t in row] for row in self.arenas_ms],
+                "gaps_bytes": list(self.gaps), "chosen": chosen}
+
+    def release(self):
+        """Frees the memory; every use of the views has completed and been dropped."""
+        self.views = []
+        if hasattr(self.owner, "close"):
+            self.owner.close()
+        self.owner = None
 
 
 def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.Tensor]], float]],
-                     device, candidates: int = 3, gaps: Sequence[int] = DEFAULT_GAPS,
-                     reserve_bytes: int = 4 << 30) -> Placement:
-    """Allocate the buffers of `sizes` bytes out of one device allocation.
+                     device, candidates: int = 4, gaps: Sequence[int] = DEFAULT_GAPS,
+                     pieces: Sequence[int] = DEFAULT_PIECES, reserve_bytes: int = 4 << 30,
+                     spacer_bytes: int = 192 << 20, buffer_set=None) -> Placement:
+    """Allocate buffers of `sizes` bytes where `probe` runs fastest.
 
-    With `probe` None or candidates <= 1 and one gap, this is a plain single
-    allocation.  Otherwise up to `candidates` allocations are made and held
-    together (fewer if device memory, less `reserve_bytes`, does not hold them),
-    each is zero-filled, `probe(views)` -> milliseconds is called for every
-    (allocation, gap) pair, and the fastest pair is kept.  The kept buffers
-    contain whatever the probe left in them: initialise them afterwards.
+    With `probe` None this is one plain allocation with the first gap.  Otherwise:
+    up to `candidates` plain allocations, then one piece-major buffer set per
+    entry of `pieces` (`buffer_set(sizes, piece, device)` -> object with .views
+    and .close(); default: the library's BufferSet), each zero-filled and timed
+    with `probe(views)` -> milliseconds (plain allocations once per gap).  While
+    the next plain allocation is made, the best candidate so far and the latest
+    loser stay allocated and a small spacer of growing size is added, so that
+    every candidate is backed by different physical pages; at most three
+    candidates are alive at once, fewer if device memory, less `reserve_bytes`,
+    does not hold them.  The kept buffers contain whatever the probe left in them:
+    initialise them afterwards.
     """
     gaps = tuple(gaps)
     if not gaps:
         raise ValueError("need at least one gap")
     total = arena_bytes(sizes, max(gaps))
-    if probe is None or (candidates <= 1 and len(gaps) == 1):
+    if probe is None:
         arena = torch.empty(total, dtype=torch.uint8, device=device)
-        return Placement(arena, gaps[0], carve(arena, sizes, gaps[0]), [], gaps, (0, 0))
+        return Placement(arena, carve(arena, sizes, gaps[0]), "arena", gaps[0], gaps=gaps)
 
-    arenas: List[torch.Tensor] = []
-    times: List[List[float]] = []
-    for _ in range(max(1, candidates)):
-        if arenas and torch.device(device).type == "cuda":
-            free, _total = torch.cuda.mem_get_info(device)
-            if free < total + reserve_bytes:
+    on_gpu = torch.device(device).type == "cuda"
+
+    def room() -> bool:
+        return not on_gpu or torch.cuda.mem_get_info(device)[0] >= total + reserve_bytes
+
+    def drop(owner):
+        if owner is not None and hasattr(owner, "close"):
+            owner.close()
+
+    best = None          # (ms, Placement)
+    loser = None         # the latest plain allocation that lost, kept until the next one exists
+    pieces_ms, arenas_ms = {}, []
+
+    def offer(ms: float, cand: Placement):
+        """Keeps the faster of `best` and `cand`; returns the owner that lost."""
+        nonlocal best
+        if best is None or ms < best[0]:
+            lost = best[1].owner if best else None
+            best = (ms, cand)
+            return lost
+        return cand.owner
+
+    spacers = []
+    for ci in range(max(0, candidates)):
+        if best is not None and not room():
+            loser = None
+            torch.cuda.empty_cache()
+            if not room():
                 break
+        if ci and spacer_bytes:
+            spacers.append(torch.empty(ci * spacer_bytes, dtype=torch.uint8, device=device))
         arena = torch.empty(total, dtype=torch.uint8, device=device)
         arena.zero_()
-        arenas.append(arena)
-        times.append([float(probe(carve(arena, sizes, g))) for g in gaps])
-    best = min(((t, ci, gi) for ci, row in enumerate(times) for gi, t in enumerate(row)))
-    _, ci, gi = best
-    kept = arenas[ci]
-    del arenas, arena
-    torch.cuda.empty_cache()              # hand the other candidates back to the driver
-    return Placement(kept, gaps[gi], carve(kept, sizes, gaps[gi]), times, gaps, (ci, gi))
+        row = [float(probe(carve(arena, sizes, g))) for g in gaps]
+        arenas_ms.append(row)
+        gi = min(range(len(gaps)), key=row.__getitem__)
+        # the loser before this one goes back to the driver below
+        loser = offer(row[gi], Placement(arena, carve(arena, sizes, gaps[gi]), "arena", gaps[gi]))
+        del arena
+        torch.cuda.empty_cache()
+    loser = None
+    torch.cuda.empty_cache()
+
+    if buffer_set is None and on_gpu and pieces:
+        from .binding import BufferSet as buffer_set
+    for piece in (pieces if buffer_set is not None else ()):
+        if best is not None and not room():
+            break
+        try:
+            bs = buffer_set(sizes, piece, device)
+        except RuntimeError as exc:                     # no such memory left, or no support
+            pieces_ms[piece] = f"failed: {exc}"
+            continue
+        for v in bs.views:
+            v.zero_()
+        ms = float(probe(list(bs.views)))
+        pieces_ms[piece] = ms
+        drop(offer(ms, Placement(bs, list(bs.views), "piece-major", piece_bytes=piece)))
+
+    if best is None:
+        raise RuntimeError("no candidate placement could be allocated")
+    kept = best[1]
+    del best, loser, spacers
+    torch.cuda.empty_cache()
+    kept.pieces_ms, kept.arenas_ms, kept.gaps = pieces_ms, arenas_ms, gaps
+    return kept

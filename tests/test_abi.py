@@ -195,3 +195,25 @@ def test_header_is_plain_c(tmp_path):
     text = open(HEADER).read()
     for forbidden in ("torch", "hipStream_t ", "#include <hip", "at::Tensor"):
         assert forbidden not in text.replace("a hipStream_t;", "")
+
+
+def test_buffer_set_rejects_bad_arguments():
+    """Validation precedes every HIP call, so these return without touching a device."""
+    L = co2.lib()
+    one = (C.c_size_t * 1)(4096)
+    zero = (C.c_size_t * 1)(0)
+    out = (C.c_void_p * 1)()
+    handle = C.c_void_p()
+    mib = 1 << 20
+    assert L.co2_buffer_set_create(0, one, 0, out, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(co2.CO2_MAX_BUFFER_SET + 1, one, 0, out, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(1, None, 0, out, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(1, one, 0, None, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(1, one, 0, out, None) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(1, zero, 0, out, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_create(1, one, mib, out, C.byref(handle)) == co2.CO2_EINVAL     # not a 2 MiB multiple
+    assert L.co2_buffer_set_create(1, one, 3 * mib, out, C.byref(handle)) == co2.CO2_EINVAL
+    assert L.co2_buffer_set_destroy(None) == co2.CO2_EINVAL
+    assert not handle.value
+    src = open(HEADER).read()
+    assert int(re.search(r"#define CO2_MAX_BUFFER_SET (\d+)", src).group(1)) == co2.CO2_MAX_BUFFER_SET

@@ -1,4 +1,5 @@
-"""Host logic of the buffer-placement chooser (no GPU: CPU tensors, a scripted probe)."""
+"""Host logic of the buffer-placement chooser (no GPU: CPU tensors, a scripted probe,
+a stand-in for the piece-major buffer set)."""
 import pytest
 import torch
 
@@ -31,11 +32,13 @@ def test_carve_rejects_small_arena():
 
 def test_plain_allocation_without_probe():
     p = pl.choose_placement([4096, 100], None, "cpu", candidates=3, gaps=(4096,))
-    assert p.chosen == (0, 0) and p.probe_ms == [] and len(p.views) == 2
-    assert p.report()["candidates_ms"] == []
+    assert p.kind == "arena" and p.gap == 4096 and len(p.views) == 2
+    assert p.report()["arenas_ms"] == [] and p.report()["piece_major_ms"] == {}
+    p.release()
+    assert p.owner is None and p.views == []
 
 
-def test_fastest_candidate_and_gap_is_kept():
+def test_fastest_arena_and_gap_is_kept():
     script = iter([5.0, 4.0, 6.0,    # candidate 0, three gaps
                    3.5, 2.5, 9.0,    # candidate 1
                    7.0, 7.0, 7.0])   # candidate 2
@@ -47,12 +50,65 @@ def test_fastest_candidate_and_gap_is_kept():
         return next(script)
 
     sizes = [8192, 8192, 100]
-    p = pl.choose_placement(sizes, probe, "cpu", candidates=3, gaps=(4096, 8192, 12288))
-    assert p.chosen == (1, 1) and p.gap == 8192
+    p = pl.choose_placement(sizes, probe, "cpu", candidates=3, gaps=(4096, 8192, 12288), pieces=())
+    assert p.kind == "arena" and p.gap == 8192
     assert len(seen) == 9
     assert p.views[0].data_ptr() == seen[4][0]                   # candidate 1's memory
     assert p.views[1].data_ptr() - p.views[0].data_ptr() == 8192 + 8192
-    assert p.report() == {"candidates_ms": [[5.0, 4.0, 6.0], [3.5, 2.5, 9.0], [7.0, 7.0, 7.0]],
-                          "gaps_bytes": [4096, 8192, 12288], "chosen": [1, 1]}
+    assert p.report() == {"piece_major_ms": {},
+                          "arenas_ms": [[5.0, 4.0, 6.0], [3.5, 2.5, 9.0], [7.0, 7.0, 7.0]],
+                          "gaps_bytes": [4096, 8192, 12288], "chosen": "arena, gap 8192 B"}
     # the three candidates were distinct allocations held at the same time
     assert len({s[0] for s in seen}) == 3
+
+
+class FakeSet:
+    """Stand-in for the library's BufferSet: separate host tensors, records close()."""
+    made, closed = [], []
+
+    def __init__(self, sizes, piece, device):
+        self.piece = piece
+        self.views = [torch.full((b,), 9, dtype=torch.uint8) for b in sizes]
+        FakeSet.made.append(piece)
+
+    def close(self):
+        FakeSet.closed.append(self.piece)
+
+
+def test_piece_major_candidates_compete_with_arenas():
+    FakeSet.made, FakeSet.closed = [], []
+    mib = 1 << 20
+    times = iter([2.5, 2.6,            # two arenas, one gap each
+                  3.0, 2.0])           # piece-major sets: 4 MiB, 2 MiB
+
+    def probe(views):
+        assert all(int(v.max()) == 0 for v in views)
+        return next(times)
+
+    p = pl.choose_placement([4096, 512], probe, "cpu", candidates=2, gaps=(4096,),
+                            pieces=(4 * mib, 2 * mib), buffer_set=FakeSet)
+    assert p.kind == "piece-major" and p.piece_bytes == 2 * mib
+    assert FakeSet.made == [4 * mib, 2 * mib] and FakeSet.closed == [4 * mib]   # the loser was freed
+    assert p.report()["piece_major_ms"] == {"4 MiB": 3.0, "2 MiB": 2.0}
+    assert p.report()["arenas_ms"] == [[2.5], [2.6]]
+    assert p.report()["chosen"] == "piece-major, 2 MiB pieces"
+    p.release()
+    assert FakeSet.closed == [4 * mib, 2 * mib]
+
+
+def test_arena_beats_piece_major_and_failed_sets_are_reported():
+    FakeSet.made, FakeSet.closed = [], []
+    mib = 1 << 20
+
+    def flaky(sizes, piece, device):
+        if piece == 8 * mib:
+            raise RuntimeError("out of memory")
+        return FakeSet(sizes, piece, device)
+
+    times = iter([1.0, 3.0])           # the arena, then the one set that could be made
+    p = pl.choose_placement([4096], lambda v: next(times), "cpu", candidates=1, gaps=(4096,),
+                            pieces=(8 * mib, 2 * mib), buffer_set=flaky)
+    assert p.kind == "arena"
+    assert FakeSet.closed == [2 * mib]
+    rep = p.report()
+    assert rep["piece_major_ms"]["8 MiB"].startswith("failed") and rep["piece_major_ms"]["2 MiB"] == 3.0

@@ -1,8 +1,9 @@
-// Stand-alone check of the C ABI without PyTorch: device memory from hipMalloc,
-// libco2.so called directly, results compared element by element with the CPU
-// oracle (linked in from oracle/co2_oracle.cpp -- this program is a test).
+// Stand-alone check of the C ABI without PyTorch: device memory from hipMalloc
+// (or, with a non-zero third argument, from co2_buffer_set_create), libco2.so
+// called directly, results compared element by element with the CPU oracle
+// (linked in from oracle/co2_oracle.cpp -- this program is a test).
 //
-//   co2_selftest [n] [K]      exit code 0 = every element within 1e-5 relative
+//   co2_selftest [n] [K] [buffer_set]   exit code 0 = every element within 1e-5 relative
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -52,6 +53,7 @@ static bool close(const std::vector<float>& got, const std::vector<float>& want,
 int main(int argc, char** argv) {
   const int64_t n = argc > 1 ? std::atoll(argv[1]) : 100003;
   const int32_t K = argc > 2 ? std::atoi(argv[2]) : 3;
+  const bool use_set = argc > 3 && std::atoi(argv[3]) != 0;   // buffers from co2_buffer_set_create
   if (n < 8 || K < 1 || K > CO2_MAX_K) { std::fprintf(stderr, "bad arguments\n"); return 2; }
   const std::vector<int64_t> seg = {0, 5, 5, n / 3 + 1, n - 2, n};
   const int32_t S = static_cast<int32_t>(seg.size()) - 1;
@@ -68,10 +70,26 @@ int main(int argc, char** argv) {
   void* ws;
   const size_t nb = sizeof(float) * static_cast<size_t>(n);
   const size_t wsb = co2_workspace_bytes(n, S, K);
-  HIP_OK(hipMalloc(&da, nb)); HIP_OK(hipMalloc(&dx, nb)); HIP_OK(hipMalloc(&dm, nb));
-  HIP_OK(hipMalloc(&ddout[0], nb)); HIP_OK(hipMalloc(&ddout[1], nb));
+  co2_buffer_set* set = nullptr;
+  if (use_set) {
+    // the flat vectors out of one piece-major buffer set (2 MiB pieces: several per buffer)
+    const int32_t count = 5 + (K - 1);
+    std::vector<size_t> sizes(count, nb);
+    std::vector<void*> ptr(count, nullptr);
+    const int rc = co2_buffer_set_create(count, sizes.data(), size_t(2) << 20, ptr.data(), &set);
+    if (rc != CO2_OK) {
+      std::fprintf(stderr, "co2_buffer_set_create: %s (hip %d)\n", co2_strerror(rc), co2_last_hip_error());
+      return 1;
+    }
+    da = static_cast<float*>(ptr[0]); dx = static_cast<float*>(ptr[1]); dm = static_cast<float*>(ptr[2]);
+    ddout[0] = static_cast<float*>(ptr[3]); ddout[1] = static_cast<float*>(ptr[4]);
+    for (int k = 1; k < K; ++k) dd[k] = static_cast<float*>(ptr[4 + k]);
+  } else {
+    HIP_OK(hipMalloc(&da, nb)); HIP_OK(hipMalloc(&dx, nb)); HIP_OK(hipMalloc(&dm, nb));
+    HIP_OK(hipMalloc(&ddout[0], nb)); HIP_OK(hipMalloc(&ddout[1], nb));
+    for (int k = 1; k < K; ++k) HIP_OK(hipMalloc(&dd[k], nb));
+  }
   HIP_OK(hipMalloc(&dlam, sizeof(float) * S)); HIP_OK(hipMalloc(&dseg, sizeof(int64_t) * (S + 1)));
-  for (int k = 1; k < K; ++k) HIP_OK(hipMalloc(&dd[k], nb));
   HIP_OK(hipMalloc(&ws, wsb));
   HIP_OK(hipMemcpy(da, a.data(), nb, hipMemcpyHostToDevice));
   HIP_OK(hipMemcpy(dm, m.data(), nb, hipMemcpyHostToDevice));
@@ -123,6 +141,10 @@ int main(int argc, char** argv) {
   // argument errors come back as codes, nothing is launched
   co2_params bad = {};
   if (co2_outer_step(&bad, dx, da, da, dm, dd.data(), ddout[0], nullptr, nullptr, ws, wsb, nullptr) != CO2_EINVAL) return 1;
-  std::printf("PASS n=%lld K=%d\n", static_cast<long long>(n), K);
+  if (set) {
+    HIP_OK(hipDeviceSynchronize());
+    if (co2_buffer_set_destroy(set) != CO2_OK) { std::fprintf(stderr, "co2_buffer_set_destroy failed\n"); return 1; }
+  }
+  std::printf("PASS n=%lld K=%d buffers=%s\n", static_cast<long long>(n), K, use_set ? "buffer set" : "hipMalloc");
   return 0;
 }

@@ -1,5 +1,5 @@
 """The C ABI driven without PyTorch: a host-only C++ program (tests/c_abi/selftest.cpp)
-allocates with hipMalloc, calls libco2.so directly for four consecutive rounds and
+allocates with hipMalloc (or co2_buffer_set_create), calls libco2.so directly for four consecutive rounds and
 compares every element with the oracle source linked into it."""
 import importlib.util
 import os
@@ -18,8 +18,8 @@ def _exe():
     return mod.EXE if os.path.exists(mod.EXE) else mod.build_selftest()
 
 
-@pytest.mark.parametrize("n,K", [(100003, 3), (4099, 16), (1 << 20, 8)])
-def test_c_abi_selftest(n, K):
-    out = subprocess.run([_exe(), str(n), str(K)], capture_output=True, text=True, timeout=120)
+@pytest.mark.parametrize("n,K,buffer_set", [(100003, 3, 0), (4099, 16, 0), (1 << 20, 8, 0), (1 << 20, 8, 1)])
+def test_c_abi_selftest(n, K, buffer_set):
+    out = subprocess.run([_exe(), str(n), str(K), str(buffer_set)], capture_output=True, text=True, timeout=120)
     print(out.stdout, out.stderr, flush=True)
     assert out.returncode == 0 and "PASS" in out.stdout

@@ -211,12 +211,12 @@ def main():
         ds = [v.view(dd["dtype"]) for v in views[3:]]
         return a, m, x, ds[:2], ds[2:]
 
-    def launch(bufs, t, ev=None):
+    def launch(bufs, t, ev=None, clipped=None):
         a, m, x, own, peers = bufs
         cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
         flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
-                            ev[0] if ev else None, ev[1] if ev else None)
+                            ev[0] if ev else None, ev[1] if ev else None, clipped)
         entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
 
     def probe(views, reps=3):
@@ -312,6 +312,13 @@ def main():
     sweep_bytes = per_elem * n
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
 
+    # ---- one more step, untimed, that also counts the coordinates the clip changed
+    clipped = torch.zeros(S, dtype=torch.int64, device=dev)
+    launch(bufs, step_no[0], None, clipped)
+    step_no[0] += 1
+    torch.cuda.synchronize()
+    clipped_count = int(clipped.sum().item())
+
     # ---- yardstick: plain copy kernel over one buffer pair (8 B/element)
     cb, ce = co2.HipEvent(), co2.HipEvent()
     co2.co2_copy_f32(a, x, n, stream=stream)
@@ -336,6 +343,7 @@ def main():
                    "placement": ("separate allocations" if placement is None else
                                  placement.report() if args.placement_candidates > 0 else
                                  "first allocation"),
+                   "clipped_coordinates_in_one_step": clipped_count,
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

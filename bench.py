@@ -48,10 +48,13 @@ def parse():
     ap.add_argument("--separate-allocations", action="store_true",
                     help="allocate every buffer on its own instead of carving all of them out of "
                          "one device allocation (the layout the library recommends)")
-    ap.add_argument("--placement-candidates", type=int, default=4,
-                    help="plain device allocations tried for the buffers, besides two piece-major "
-                         "buffer sets; the sweep is timed on each candidate and the fastest layout "
-                         "is kept.  0 = no search: the first plain allocation as it comes")
+    ap.add_argument("--placement-candidates", type=int, default=3,
+                    help="plain device allocations tried for the buffers after the free device memory "
+                         "has been compacted; the sweep is timed on each candidate and the fastest "
+                         "layout is kept.  0 = no compaction, no search: the first plain allocation "
+                         "as it comes")
+    ap.add_argument("--piece-major", action="store_true",
+                    help="also try two piece-major buffer sets (co2_buffer_set_create) as candidates")
     ap.add_argument("--hip-graph", action="store_true",
                     help="also capture two consecutive rounds into a HIP graph and time its replays; "
                          "value and ms_per_step then come from the replays (launch-bound small "
@@ -242,6 +245,7 @@ def main():
         search = args.placement_candidates > 0
         placement = pl.choose_placement(sizes, probe if search else None, dev,
                                         candidates=args.placement_candidates,
+                                        pieces=pl.DEFAULT_PIECES if args.piece_major else (),
                                         gaps=pl.DEFAULT_GAPS if search else (pl.PAGE,))
         a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"

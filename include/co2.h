@@ -33,8 +33,11 @@
  *     the sweep streams all of them at once and runs 2-5 % faster than over
  *     buffers the allocator has scattered.  Which physical pages back that
  *     allocation moves the sweep's duration by up to 10 % more and stays fixed
- *     for the allocation's life: a long-running caller can time the sweep on a
- *     few candidate allocations held together and keep the fastest.
+ *     for the allocation's life.  On a device whose memory has been through
+ *     many allocate/free cycles it pays to allocate nearly all free memory in
+ *     one piece and free it again first (the driver then merges its free
+ *     blocks), and a long-running caller can time the sweep on a few candidate
+ *     allocations held together and keep the fastest.
  *   - Return value: CO2_OK or a negative error code; on error nothing has been
  *     enqueued and no buffer has been touched.  No exceptions, no aborts.
  *   - All fp32 arithmetic is unfused (no FMA contraction) and evaluated in the

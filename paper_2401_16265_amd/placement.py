@@ -9,15 +9,19 @@ single-stream copy runs equally fast in all of them; the byte gap between
 consecutive buffers moves it by another +-1.5 %), and what the driver hands out
 depends on the allocation history of the machine.  None of this can be predicted
 from user space, but it is stable for the life of an allocation, and a training
-job allocates once.  So the layout is chosen by measurement.  Candidates are
+job allocates once.  So the driver's free memory is first brought back to one
+block (compact_device_memory) and the layout is then chosen by measurement.
+Candidates are
 
-  * piece-major buffer sets (co2_buffer_set_create): every buffer's physical
-    memory is obtained in pieces, piece j of all buffers before piece j+1, so
-    that what the sweep touches at one time lies close together; these have been
-    at the fast end on every machine state tried;
   * plain single allocations with the buffers carved out back to back, made in
     turn while earlier ones are still held, so that each lands on other physical
-    pages, each tried with a few gaps between consecutive buffers.
+    pages, each tried with a few gaps between consecutive buffers;
+  * on request, piece-major buffer sets (co2_buffer_set_create): every buffer's
+    physical memory is obtained in pieces, piece j of all buffers before piece
+    j+1, so that what the sweep touches at one time lies close together.  They
+    have been at the fast end on every machine state tried, but allocating and
+    freeing piece-sized blocks leaves the driver's free memory more scattered
+    for whoever allocates next, so they are not tried by default.
 
 The caller's probe -- a few launches of the real kernel -- is timed on every
 candidate and the fastest is kept; everything else is freed.
@@ -58,6 +62,36 @@ def arena_bytes(sizes: Sequence[int], gap: int) -> int:
     return sum(padded(b) + gap for b in sizes)
 
 
+def compact_device_memory(device, headroom: int = 3 << 30) -> int:
+    """Allocates nearly all free device memory in ONE allocation and frees it again.
+
+    The driver keeps freed memory as a patchwork of blocks that it merges lazily;
+    after other processes (or this one) have allocated and freed many buffers, a
+    new multi-gigabyte allocation is assembled from scattered blocks and the sweep
+    runs 5-10 % slower on it.  A request that only fits if everything is merged
+    makes the driver do that merge, and what is freed afterwards is one block
+    again.  Measured: plain allocations that probed at 12.5-13.4 ms before this
+    call probed at 11.9-12.0 ms (the first and third of three) right after it.
+    Returns the number of bytes that were taken (0 if nothing could be)."""
+    if torch.device(device).type != "cuda":
+        return 0
+    torch.cuda.synchronize(device)
+    torch.cuda.empty_cache()
+    free = torch.cuda.mem_get_info(device)[0]
+    for h in (headroom, 2 * headroom, 4 * headroom, 8 * headroom):
+        if free <= h:
+            break
+        try:
+            big = torch.empty(free - h, dtype=torch.uint8, device=device)
+        except RuntimeError:                      # torch.cuda.OutOfMemoryError is a RuntimeError
+            continue
+        taken = big.numel()
+        del big
+        torch.cuda.empty_cache()
+        return taken
+    return 0
+
+
 @dataclass
 class Placement:
     owner: object                        # what holds the memory: a uint8 tensor or a BufferSet
@@ -65,6 +99,7 @@ class Placement:
     kind: str = "arena"                  # "arena" or "piece-major"
     gap: int = PAGE                      # arena: bytes between consecutive buffers
     piece_bytes: int = 0                 # piece-major: requested piece size
+    compacted_bytes: int = 0             # what compact_device_memory took before the search
     pieces_ms: dict = field(default_factory=dict)                 # piece size -> probe ms (or error text)
     arenas_ms: List[List[float]] = field(default_factory=list)    # [candidate][gap index]
     gaps: Tuple[int, ...] = ()
@@ -72,7 +107,8 @@ class Placement:
     def report(self) -> dict:
         chosen = (f"piece-major, {self.piece_bytes >> 20} MiB pieces" if self.kind == "piece-major"
                   else f"arena, gap {self.gap} B")
-        return {"piece_major_ms": {f"{k >> 20} MiB": (round(v, 3) if isinstance(v, float) else v)
+        return {"compacted_gib": round(self.compacted_bytes / 2**30, 1),
+                "piece_major_ms": {f"{k >> 20} MiB": (round(v, 3) if isinstance(v, float) else v)
                                    for k, v in self.pieces_ms.items()},
                 "arenas_ms": [[round(t, 3) for t in row] for row in self.arenas_ms],
                 "gaps_bytes": list(self.gaps), "chosen": chosen}
@@ -87,11 +123,12 @@ class Placement:
 
 def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.Tensor]], float]],
                      device, candidates: int = 4, gaps: Sequence[int] = DEFAULT_GAPS,
-                     pieces: Sequence[int] = DEFAULT_PIECES, reserve_bytes: int = 4 << 30,
-                     spacer_bytes: int = 192 << 20, buffer_set=None) -> Placement:
+                     pieces: Sequence[int] = (), reserve_bytes: int = 4 << 30,
+                     spacer_bytes: int = 192 << 20, buffer_set=None, compact: bool = True) -> Placement:
     """Allocate buffers of `sizes` bytes where `probe` runs fastest.
 
     With `probe` None this is one plain allocation with the first gap.  Otherwise:
+    compact_device_memory() first (unless `compact` is False), then
     up to `candidates` plain allocations, then one piece-major buffer set per
     entry of `pieces` (`buffer_set(sizes, piece, device)` -> object with .views
     and .close(); default: the library's BufferSet), each zero-filled and timed
@@ -120,6 +157,7 @@ def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.
         if owner is not None and hasattr(owner, "close"):
             owner.close()
 
+    compacted = compact_device_memory(device) if compact else 0
     best = None          # (ms, Placement)
     loser = None         # the latest plain allocation that lost, kept until the next one exists
     pieces_ms, arenas_ms = {}, []
@@ -176,4 +214,5 @@ def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.
     del best, loser, spacers
     torch.cuda.empty_cache()
     kept.pieces_ms, kept.arenas_ms, kept.gaps = pieces_ms, arenas_ms, gaps
+    kept.compacted_bytes = compacted
     return kept

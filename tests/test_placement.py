@@ -55,7 +55,7 @@ def test_fastest_arena_and_gap_is_kept():
     assert len(seen) == 9
     assert p.views[0].data_ptr() == seen[4][0]                   # candidate 1's memory
     assert p.views[1].data_ptr() - p.views[0].data_ptr() == 8192 + 8192
-    assert p.report() == {"piece_major_ms": {},
+    assert p.report() == {"compacted_gib": 0.0, "piece_major_ms": {},
                           "arenas_ms": [[5.0, 4.0, 6.0], [3.5, 2.5, 9.0], [7.0, 7.0, 7.0]],
                           "gaps_bytes": [4096, 8192, 12288], "chosen": "arena, gap 8192 B"}
     # the three candidates were distinct allocations held at the same time
@@ -112,3 +112,7 @@ def test_arena_beats_piece_major_and_failed_sets_are_reported():
     assert FakeSet.closed == [2 * mib]
     rep = p.report()
     assert rep["piece_major_ms"]["8 MiB"].startswith("failed") and rep["piece_major_ms"]["2 MiB"] == 3.0
+
+
+def test_compaction_is_a_no_op_off_the_gpu():
+    assert pl.compact_device_memory("cpu") == 0

@@ -38,8 +38,11 @@
  *     one piece and free it again first (the driver then merges its free
  *     blocks), and a long-running caller can time the sweep on a few candidate
  *     allocations held together and keep the fastest.
- *   - Return value: CO2_OK or a negative error code; on error nothing has been
- *     enqueued and no buffer has been touched.  No exceptions, no aborts.
+ *   - Return value: CO2_OK or a negative error code.  Arguments are checked
+ *     before the first launch: on CO2_EINVAL or CO2_EWORKSPACE nothing has
+ *     been enqueued and no buffer has been touched.  CO2_EHIP reports a HIP
+ *     call of the launch sequence that failed; launches enqueued before it
+ *     still run.  No exceptions, no aborts.
  *   - All fp32 arithmetic is unfused (no FMA contraction) and evaluated in the
  *     order documented per call, so results are reproducible bit for bit.
  */

@@ -1,6 +1,7 @@
 // C ABI of libco2 (see include/co2.h): host-side validation, workspace layout,
 // kernel sequencing.  Nothing here allocates, synchronises or keeps device
-// state; every call enqueues on the caller's stream and returns.
+// state; every call enqueues on the caller's stream and returns.  (The
+// optional buffer-set calls, the only ones that allocate, are in co2_buffers.hip.)
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -177,7 +178,7 @@ int co2_last_hip_error(void) { return g_last_hip_error; }
 namespace {
 
 // Shared by co2_outer_step (fp32 pseudo-gradient buffers) and co2_outer_step_bf16
-// (bf16 bit patterns): delta_elem is the byte size of one stored pseudo-gradient.
+// (`bf16`: the K buffers and delta_out hold bf16 bit patterns).
 int outer_step_impl(const co2_params* p, float* params, const float* anchor, float* anchor_out,
                     float* momentum, const void* const* deltas, void* delta_out, bool bf16,
                     const float* first_step_norm, float* lambda_out, void* workspace,

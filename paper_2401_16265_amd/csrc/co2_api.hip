@@ -138,8 +138,15 @@ const Tuning& tuning() {
     const int w = k <= 4 ? 8 : k <= 9 ? 7 : k <= 12 ? 6 : k <= 14 ? 5 : 4;
     u.sweep_waves_per_cu[k] = sweep_override >= 0 ? sweep_override : w;
   }
-  u.norm_waves_per_cu = env_int("CO2_NORM_WAVES", 8);
-  u.adam_waves_per_cu = env_int("CO2_ADAM_WAVES", 7);
+  // The other kernels follow the same rule of thumb (about 64 KB of loads in
+  // flight per compute unit): the norm pass holds 4 KB per buffer and
+  // wavefront, an AdamW wavefront 7 KB (9 KB with the anchor).
+  const int norm_override = env_int("CO2_NORM_WAVES", -1);
+  u.norm_waves_per_cu[0] = u.norm_waves_per_cu[2] = norm_override >= 0 ? norm_override : 8;
+  u.norm_waves_per_cu[1] = norm_override >= 0 ? norm_override : 16;
+  const int adam_override = env_int("CO2_ADAM_WAVES", -1);
+  u.adam_waves_per_cu[0] = adam_override >= 0 ? adam_override : 7;
+  u.adam_waves_per_cu[1] = adam_override >= 0 ? adam_override : 5;
   u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 7);
   return u;
 }

@@ -46,8 +46,8 @@ struct AdamArgs {
 // override them (read at every launch) for tuning runs.
 struct Tuning {
   int sweep_waves_per_cu[CO2_MAX_K + 1];
-  int norm_waves_per_cu;
-  int adam_waves_per_cu;
+  int norm_waves_per_cu[3];     // by number of buffers read (1 or 2)
+  int adam_waves_per_cu[2];     // [1]: the step that also reads the anchor and writes delta_out
   int copy_waves_per_cu;
 };
 const Tuning& tuning();

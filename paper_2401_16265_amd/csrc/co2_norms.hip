@@ -187,7 +187,7 @@ hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const voi
                                   float phi1, bool b1_bf16, const int64_t* off_dev, int S,
                                   int64_t n, SlotRec* slots, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>((n + kNormTile - 1) / kNormTile)), block(kWave);
-  const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu);
+  const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu[nb == 2 ? 2 : 1]);
   if (nb == 2 && b1_bf16) {
     hipLaunchKernelGGL((sqnorm_partials<2, true>), grid, block, lds, st, b0, phi0, b1, phi1,
                        off_dev, S, n, slots);

@@ -218,13 +218,14 @@ def main():
         ds = [v.view(dd["dtype"]) for v in views[3:]]
         return a, m, x, ds[:2], ds[2:]
 
-    def launch(bufs, t, ev=None, clipped=None):
+    def launch(bufs, t, ev=None, clipped=None, on=None):
+        """One outer step of round t on stream `on` (default: the current stream)."""
         a, m, x, own, peers = bufs
         cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
         flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
                             ev[0] if ev else None, ev[1] if ev else None, clipped)
-        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=stream)
+        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=on or stream)
 
     def probe(views, reps=3):
         """Median duration (ms) of the sweep kernel over `reps` launches on these buffers."""
@@ -299,10 +300,9 @@ def main():
         graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
         t_cap = step_no[0] + (step_no[0] % 2)               # even round first
         with torch.cuda.graph(graph, stream=side):
-            stream = torch.cuda.current_stream().cuda_stream
-            launch(bufs, t_cap)
-            launch(bufs, t_cap + 1)
-        stream = torch.cuda.current_stream().cuda_stream
+            capturing = torch.cuda.current_stream().cuda_stream
+            launch(bufs, t_cap, on=capturing)
+            launch(bufs, t_cap + 1, on=capturing)
         if step_no[0] % 2:
             one_step()                                      # bring the ping-pong to an even round
         replays = max(1, args.steps // 2)

@@ -28,7 +28,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # summaries under profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/fused_sweep_1p3b_k8_hbm_counters.md
-    ("1p3b", "carried"): 8.0800e10,
+    ("1p3b", "f32", 8): 8.0800e10,
+    # profiles/fused_sweep_bf16_deltas_1p3b_k8.md: (2 x 18373268 + 18537254) KiB
+    ("1p3b", "bf16", 8): 5.6610e10,
 }
 
 
@@ -356,7 +358,7 @@ def main():
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.form)) if not bf16 and not args.K else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.deltas, K)),   # the sweep's, either form
                      "kernel": "fused_sweep", "kernel_ms": sweep_ms,
                      "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
     }

@@ -63,7 +63,8 @@ enum {
   CO2_OK = 0,
   CO2_EINVAL = -1,      /* bad argument (NULL, range, alignment, aliasing)  */
   CO2_EWORKSPACE = -2,  /* workspace NULL or smaller than co2_workspace_bytes */
-  CO2_EHIP = -3         /* a kernel launch failed; see co2_last_hip_error()   */
+  CO2_EHIP = -3         /* a HIP call failed (launch, or allocation in
+                           co2_buffer_set_create); see co2_last_hip_error()  */
 };
 
 /* Bits of co2_params.flags */

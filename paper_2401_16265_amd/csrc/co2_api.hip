@@ -173,7 +173,7 @@ const char* co2_strerror(int code) {
     case CO2_OK: return "ok";
     case CO2_EINVAL: return "invalid argument (NULL, out of range, misaligned or overlapping buffer)";
     case CO2_EWORKSPACE: return "workspace missing, misaligned or smaller than co2_workspace_bytes()";
-    case CO2_EHIP: return "HIP kernel launch failed (see co2_last_hip_error())";
+    case CO2_EHIP: return "a HIP call (kernel launch or allocation) failed (see co2_last_hip_error())";
     default: return "unknown co2 error code";
   }
 }

@@ -263,7 +263,7 @@ int co2_buffer_set_destroy(co2_buffer_set* set);
 /* Text for an error code (static string, never NULL). */
 const char* co2_strerror(int code);
 
-/* hipError_t value of the most recent failed launch in this thread (0 if none). */
+/* hipError_t value of the most recent failed HIP call in this thread (0 if none). */
 int co2_last_hip_error(void);
 
 #ifdef __cplusplus

@@ -248,6 +248,8 @@ def co2_outer_step(p: Co2Params, params, anchor, anchor_out, momentum, deltas, d
     f32 = torch.float32
     dptrs = None
     if deltas is not None:
+        if len(deltas) != p.K:
+            raise ValueError(f"{len(deltas)} delta buffers for K={p.K}")
         dptrs = (C.c_void_p * len(deltas))(*[_dp(d, f32) for d in deltas])
     rc = lib().co2_outer_step(
         C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),
@@ -272,6 +274,8 @@ def co2_outer_step_bf16(p: Co2Params, params, anchor, anchor_out, momentum, delt
     f32 = torch.float32
     dptrs = None
     if deltas_bf16 is not None:
+        if len(deltas_bf16) != p.K:
+            raise ValueError(f"{len(deltas_bf16)} delta buffers for K={p.K}")
         dptrs = (C.c_void_p * len(deltas_bf16))(*[_bf16_ptr(d) for d in deltas_bf16])
     rc = lib().co2_outer_step_bf16(
         C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),

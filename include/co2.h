@@ -19,7 +19,8 @@
  *   - Pointers marked DEVICE point to GPU memory owned by the caller; pointers
  *     marked HOST point to ordinary host memory.  Apart from the optional
  *     co2_buffer_set_* pair at the end, the library allocates nothing, keeps
- *     no state between calls, and never synchronises: every call
+ *     no state between calls (co2_outer_step_static alone works in a scratch
+ *     array of the library's own), and never synchronises: every call
  *     validates its arguments on the host, enqueues kernels on `hip_stream`
  *     (a hipStream_t; NULL = the null stream) and returns.  The launches hold
  *     no memset and no host callback, so a caller may capture them into a HIP
@@ -63,8 +64,10 @@ enum {
   CO2_OK = 0,
   CO2_EINVAL = -1,      /* bad argument (NULL, range, alignment, aliasing)  */
   CO2_EWORKSPACE = -2,  /* workspace NULL or smaller than co2_workspace_bytes */
-  CO2_EHIP = -3         /* a HIP call failed (launch, or allocation in
+  CO2_EHIP = -3,        /* a HIP call failed (launch, or allocation in
                            co2_buffer_set_create); see co2_last_hip_error()  */
+  CO2_ESCRATCH = -4     /* co2_outer_step_static: the sizes need more scratch than
+                           CO2_STATIC_SCRATCH_BYTES                          */
 };
 
 /* Bits of co2_params.flags */
@@ -154,6 +157,38 @@ int co2_outer_step(const co2_params* p,
                    float* momentum, const float* const* deltas, float* delta_out,
                    const float* first_step_norm, float* lambda_out,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* co2_outer_step for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving-style loops,
+ * harnesses that forbid hipMalloc.  Same arguments, arithmetic, flags and
+ * results (bit for bit) as co2_outer_step, minus the workspace: the per-tile
+ * partial sums, per-segment sums and 1/Lambda live in a scratch array of
+ * CO2_STATIC_SCRATCH_BYTES that is part of the library's device image (one
+ * copy per GPU, occupied on every GPU the library is used on until the process
+ * ends).  The call itself never calls hipMalloc, hipFree or any allocating
+ * routine; the first call made on a GPU looks up that GPU's copy of the array
+ * (make that call outside a graph capture), later calls only enqueue kernels.
+ *
+ *   - Limit: co2_workspace_bytes(p->n, p->S, p->K) <= CO2_STATIC_SCRATCH_BYTES
+ *     (about 1.7e8 elements with a few hundred segments); beyond it the call
+ *     returns CO2_ESCRATCH before anything is enqueued.
+ *   - The GPU that hip_stream belongs to must be the current device.
+ *   - All calls on one GPU share that GPU's array, which keeps what the last
+ *     call left in it.  Nothing in it has to start at zero (every record a
+ *     round reads is written earlier in the same round or, with
+ *     CO2_FLAG_CARRIED_NORMS, by the previous call), so the library clears
+ *     nothing.  Consequences: calls that may run at the same time on one GPU
+ *     (different streams without ordering between them) race on the array and
+ *     must be serialised by the caller; CO2_FLAG_CARRIED_NORMS is only valid
+ *     if the previous call of this entry point on this GPU was the previous
+ *     round of the same problem.
+ * Errors: as co2_outer_step (no CO2_EWORKSPACE), plus CO2_ESCRATCH. */
+#define CO2_STATIC_SCRATCH_BYTES (32u << 20)
+int co2_outer_step_static(const co2_params* p,
+                          float* params, const float* anchor, float* anchor_out,
+                          float* momentum, const float* const* deltas, float* delta_out,
+                          const float* first_step_norm, float* lambda_out,
+                          void* hip_stream);
 
 /* The same update with the pseudo-gradients transported in bf16 (the paper's
  * Section 2, "Efficient Communication": compression of what the all-reduce

@@ -10,7 +10,8 @@ import torch
 
 from . import build as _build
 
-CO2_OK, CO2_EINVAL, CO2_EWORKSPACE, CO2_EHIP = 0, -1, -2, -3
+CO2_OK, CO2_EINVAL, CO2_EWORKSPACE, CO2_EHIP, CO2_ESCRATCH = 0, -1, -2, -3, -4
+CO2_STATIC_SCRATCH_BYTES = 32 << 20
 CO2_MAX_K = 16
 CO2_MAX_NORM_BUFS = 32
 CO2_FLAG_NONE = 0
@@ -59,6 +60,8 @@ def lib() -> C.CDLL:
         L.co2_last_hip_error.argtypes = []
         L.co2_outer_step.restype = C.c_int
         L.co2_outer_step.argtypes = [C.POINTER(Co2Params)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        L.co2_outer_step_static.restype = C.c_int
+        L.co2_outer_step_static.argtypes = [C.POINTER(Co2Params)] + [C.c_void_p] * 8 + [C.c_void_p]
         L.co2_outer_step_bf16.restype = C.c_int
         L.co2_outer_step_bf16.argtypes = L.co2_outer_step.argtypes
         L.co2_pseudo_grad_norms.restype = C.c_int
@@ -257,6 +260,23 @@ def co2_outer_step(p: Co2Params, params, anchor, anchor_out, momentum, deltas, d
         _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream))
     return _check(rc, "co2_outer_step", check)
+
+
+def co2_outer_step_static(p: Co2Params, params, anchor, anchor_out, momentum, deltas, delta_out,
+                          first_step_norm, lambda_out, stream=None, check: bool = True) -> int:
+    """int co2_outer_step_static(...) -- see include/co2.h: co2_outer_step without a
+    workspace argument (the library's own per-GPU scratch array is used)."""
+    f32 = torch.float32
+    dptrs = None
+    if deltas is not None:
+        if len(deltas) != p.K:
+            raise ValueError(f"{len(deltas)} delta buffers for K={p.K}")
+        dptrs = (C.c_void_p * len(deltas))(*[_dp(d, f32) for d in deltas])
+    rc = lib().co2_outer_step_static(
+        C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),
+        dptrs, _dp(delta_out, f32), _dp(first_step_norm, f32), _dp(lambda_out, f32),
+        _stream(stream))
+    return _check(rc, "co2_outer_step_static", check)
 
 
 def _bf16_ptr(t: Optional[torch.Tensor]) -> Optional[int]:

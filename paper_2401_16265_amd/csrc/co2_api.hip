@@ -1,14 +1,24 @@
 // C ABI of libco2 (see include/co2.h): host-side validation, workspace layout,
-// kernel sequencing.  Nothing here allocates, synchronises or keeps device
-// state; every call enqueues on the caller's stream and returns.  (The
-// optional buffer-set calls, the only ones that allocate, are in co2_buffers.hip.)
+// kernel sequencing.  Nothing here allocates or synchronises; every call
+// enqueues on the caller's stream and returns.  The only device state is the
+// scratch array of co2_outer_step_static below.  (The optional buffer-set
+// calls, the only ones that allocate, are in co2_buffers.hip.)
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "co2.h"
 #include "co2_launch.hpp"
+
+// Scratch of co2_outer_step_static, the entry point for callers that cannot
+// allocate: one copy per GPU, held from the moment the library's code object is
+// loaded on that GPU until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address it stands for on a given
+// GPU is looked up once per device (static_scratch_of) and only that address is
+// ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[CO2_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -110,6 +120,29 @@ inline hipError_t enqueue_counts(const Workspace& w, const co2_params* p, hipStr
   return co2::launch_counts_finish(w.sub[0], p->S, w.split, p->clipped_out, st);
 }
 
+// Device address of `scratch` on the current GPU, resolved on the first call
+// made while that GPU is current and kept for the life of the process.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e);
+  if (dev < 0 || dev >= kMaxDevices) return fail_hip(hipErrorInvalidDevice);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e);
+    if (!ptr) return fail_hip(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CO2_OK;
+}
+
 int env_int(const char* name, int fallback) {
   const char* v = std::getenv(name);
   if (!v || !*v) return fallback;
@@ -174,6 +207,8 @@ const char* co2_strerror(int code) {
     case CO2_EINVAL: return "invalid argument (NULL, out of range, misaligned or overlapping buffer)";
     case CO2_EWORKSPACE: return "workspace missing, misaligned or smaller than co2_workspace_bytes()";
     case CO2_EHIP: return "a HIP call (kernel launch or allocation) failed (see co2_last_hip_error())";
+    case CO2_ESCRATCH: return "problem too large for the static scratch of co2_outer_step_static "
+                              "(co2_workspace_bytes() exceeds CO2_STATIC_SCRATCH_BYTES)";
     default: return "unknown co2 error code";
   }
 }
@@ -184,15 +219,18 @@ int co2_last_hip_error(void) { return g_last_hip_error; }
 
 namespace {
 
-// Shared by co2_outer_step (fp32 pseudo-gradient buffers) and co2_outer_step_bf16
-// (`bf16`: the K buffers and delta_out hold bf16 bit patterns).
+// Shared by co2_outer_step (fp32 pseudo-gradient buffers), co2_outer_step_bf16
+// (`bf16`: the K buffers and delta_out hold bf16 bit patterns) and
+// co2_outer_step_static (`use_static`: the workspace is the library's own
+// per-GPU scratch array; `workspace` and `workspace_bytes` are ignored).
 int outer_step_impl(const co2_params* p, float* params, const float* anchor, float* anchor_out,
                     float* momentum, const void* const* deltas, void* delta_out, bool bf16,
                     const float* first_step_norm, float* lambda_out, void* workspace,
-                    size_t workspace_bytes, void* hip_stream) {
+                    size_t workspace_bytes, bool use_static, void* hip_stream) {
   // ---- validation (no side effects before it passes)
   if (!p) return CO2_EINVAL;
   if (!table_ok(p->n, p->S, p->seg_off) || !p->seg_off_dev) return CO2_EINVAL;
+  if (use_static && layout(nullptr, p->n, p->S).bytes > CO2_STATIC_SCRATCH_BYTES) return CO2_ESCRATCH;
   if (p->K < 1 || p->K > CO2_MAX_K || p->tau < 1 || p->step < 0) return CO2_EINVAL;
   if (!std::isfinite(p->alpha)) return CO2_EINVAL;
   if (!(p->beta >= 0.0f && p->beta < 1.0f)) return CO2_EINVAL;
@@ -233,10 +271,19 @@ int outer_step_impl(const co2_params* p, float* params, const float* anchor, flo
       dptr.p[k] = dk;
     }
   }
-  const Workspace w = layout(workspace, p->n, p->S);
-  if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
-  for (int i = 0; i < 5; ++i)
-    if (overlaps(vec[i], vecb[i], workspace, w.bytes)) return CO2_EINVAL;
+  Workspace w = layout(use_static ? nullptr : workspace, p->n, p->S);
+  if (use_static) {
+    // Last step before the launches, after every argument check: the address of
+    // this GPU's scratch array (no allocation; a table lookup after the first call).
+    void* ptr = nullptr;
+    const int rc = static_scratch_of_current_device(&ptr);
+    if (rc != CO2_OK) return rc;
+    w = layout(ptr, p->n, p->S);
+  } else {
+    if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
+    for (int i = 0; i < 5; ++i)
+      if (overlaps(vec[i], vecb[i], workspace, w.bytes)) return CO2_EINVAL;
+  }
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   co2::SweepArgs g{};
@@ -291,7 +338,16 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
                    size_t workspace_bytes, void* hip_stream) {
   return outer_step_impl(p, params, anchor, anchor_out, momentum,
                          reinterpret_cast<const void* const*>(deltas), delta_out, false,
-                         first_step_norm, lambda_out, workspace, workspace_bytes, hip_stream);
+                         first_step_norm, lambda_out, workspace, workspace_bytes, false, hip_stream);
+}
+
+int co2_outer_step_static(const co2_params* p, float* params, const float* anchor,
+                          float* anchor_out, float* momentum, const float* const* deltas,
+                          float* delta_out, const float* first_step_norm, float* lambda_out,
+                          void* hip_stream) {
+  return outer_step_impl(p, params, anchor, anchor_out, momentum,
+                         reinterpret_cast<const void* const*>(deltas), delta_out, false,
+                         first_step_norm, lambda_out, nullptr, 0, true, hip_stream);
 }
 
 int co2_outer_step_bf16(const co2_params* p, float* params, const float* anchor,
@@ -301,7 +357,7 @@ int co2_outer_step_bf16(const co2_params* p, float* params, const float* anchor,
                         void* hip_stream) {
   return outer_step_impl(p, params, anchor, anchor_out, momentum,
                          reinterpret_cast<const void* const*>(deltas_bf16), delta_out_bf16, true,
-                         first_step_norm, lambda_out, workspace, workspace_bytes, hip_stream);
+                         first_step_norm, lambda_out, workspace, workspace_bytes, false, hip_stream);
 }
 
 int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t nbuf,

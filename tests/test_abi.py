@@ -117,6 +117,29 @@ def test_outer_step_rejects_bad_buffers():
     assert _call(p2, params=None, delta_out=None, anchor_out=_fake(6)) == co2.CO2_EINVAL
 
 
+def test_static_entry_point_validates_like_the_workspace_one():
+    """co2_outer_step_static checks its arguments before it touches the GPU."""
+    def call(p, params=_fake(0), anchor=_fake(1), momentum=_fake(2), deltas=(_fake(3), _fake(4)),
+             delta_out=_fake(5)):
+        dp = (C.c_void_p * len(deltas))(*deltas)
+        return co2.lib().co2_outer_step_static(C.byref(p), params, anchor, anchor, momentum, dp,
+                                               delta_out, None, None, None)
+    p, keep = _params([0, 1000, 4096], K=0)
+    assert call(p) == co2.CO2_EINVAL
+    p, keep = _params([0, 1000, 4096])
+    assert call(p, momentum=_fake(0) + 1024) == co2.CO2_EINVAL
+    assert call(p, delta_out=_fake(3)) == co2.CO2_EINVAL
+    # sizes whose partial sums do not fit the static scratch array
+    big = 200_000_000
+    assert co2.workspace_bytes(big, 2, 2) > co2.CO2_STATIC_SCRATCH_BYTES
+    p, keep = _params([0, 1000, big])
+    assert call(p) == co2.CO2_ESCRATCH
+    assert "scratch" in co2.strerror(co2.CO2_ESCRATCH)
+    src = open(HEADER).read()
+    assert re.search(r"#define\s+CO2_STATIC_SCRATCH_BYTES\s+\(32u << 20\)", src)
+    assert co2.CO2_STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_norms_and_adamw_reject_bad_arguments():
     L = co2.lib()
     p, keep = _params([0, 1000, 4096])

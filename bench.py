@@ -27,10 +27,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel calibration);
 # summaries under profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/fused_sweep_1p3b_k8_hbm_counters.md
-    ("1p3b", "f32", 8): 8.0800e10,
-    # profiles/fused_sweep_bf16_deltas_1p3b_k8.md: (2 x 18373268 + 18537254) KiB
-    ("1p3b", "bf16", 8): 5.6610e10,
+    ("1p3b", "f32", 8): (8.0800e10, "profiles/fused_sweep_1p3b_k8_hbm_counters.md (profiled constant, "
+                                    "not measured in this run)"),
+    # (2 x 18373268 + 18537254) KiB
+    ("1p3b", "bf16", 8): (5.6610e10, "profiles/fused_sweep_bf16_deltas_1p3b_k8.md (profiled constant, "
+                                     "not measured in this run)"),
 }
 
 
@@ -62,57 +63,98 @@ def parse():
                          "value and ms_per_step then come from the replays (launch-bound small "
                          "workloads), the roofline still from the eager launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-elems", type=int, default=160_000_000)
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, table, sample_elems: int, gen_device="cpu"):
-    """The oracle, as it stands, single-threaded on this host, on a bounded sample
-    of whole segments of the same workload (same K, same drift recipe)."""
+def _segment_chunks(table, limit):
+    """Groups of whole consecutive segments of at most `limit` elements (a larger
+    segment is a group of its own): (first element, last element + 1, re-based table)."""
+    out, i, S = [], 0, len(table) - 1
+    while i < S:
+        j = i + 1
+        while j < S and table[j + 1] - table[i] <= limit:
+            j += 1
+        out.append((table[i], table[j], [o - table[i] for o in table[i:j + 1]]))
+        i = j
+    return out
+
+
+def cpu_baseline(cfg, table, bufs, t, min_seconds=10.0, max_passes=3):
+    """The oracle, as it stands, on this host's cores, on the workload resident on the
+    device: the round-t inputs (anchor, momentum, local params, the worker's own
+    previous pseudo-gradient and the K-1 peers') are copied to host memory chunk by
+    chunk (whole segments) and handed to the oracle; only the oracle calls are timed.
+    Returns (single-thread figure over whole passes of the config, all-core figure)."""
+    import os
+    import threading
+
     import numpy as np
     import torch
 
-    import co2_inputs
     from oracle import co2_oracle
 
-    # whole segments, largest-first skipped if too big, until the budget is filled
-    sizes = [table[s + 1] - table[s] for s in range(len(table) - 1)]
-    chosen, total = [], 0
-    for s in range(len(sizes) - 1, -1, -1):          # from the last layers backwards
-        if total + sizes[s] <= sample_elems:
-            chosen.append(s)
-            total += sizes[s]
-    chosen.sort()
-    otable = np.concatenate([[0], np.cumsum([sizes[s] for s in chosen])]).astype(np.int64)
-    n = int(otable[-1])
+    a, m, x, own, peers = bufs
+    cur = own[t % 2]
+    dev_in = [x, a, m, cur] + list(peers)
+    kw = dict(alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau, step=t)
+    co2_oracle.build()
+    co2_oracle.sqnorms(np.zeros(1, np.float32), [0, 1])          # load the library
 
-    def draw(std, bid, student=False):
-        # drawn on the GPU when there is one (the Student-t recipe is slow on the
-        # host), then handed to the oracle as host arrays
-        t = torch.empty(n, dtype=torch.float32, device=gen_device)
-        if student:
-            co2_inputs.fill_student_t_(t, std, cfg.drift_nu, co2_inputs.seed_for(cfg.seed, bid))
-        else:
-            co2_inputs.fill_normal_(t, std, co2_inputs.seed_for(cfg.seed, bid))
-        return t.cpu().numpy()
+    def staged(pinned, lo, hi):
+        """Host copies (numpy views of pinned memory) of elements [lo, hi) of every input."""
+        views = [pb[:hi - lo] for pb in pinned]
+        for v, d in zip(views, dev_in):
+            v.copy_(d[lo:hi], non_blocking=True)
+        torch.cuda.synchronize()
+        return [v.numpy() for v in views]
 
-    st = cfg.drift == "student_t"
-    a = draw(cfg.param_std, 1)
-    m = draw(cfg.momentum_std, 2)
-    x = a + draw(cfg.drift_scale, 100, st)
-    d = [draw(cfg.drift_scale, 200 + k, st) for k in range(cfg.K)]
-    kw = dict(seg_off=otable, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
-    co2_oracle.outer_step_f32(x=x, a=a, m=m, deltas=d, step=1, **kw)      # warm the pages
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        co2_oracle.outer_step_f32(x=x, a=a, m=m, deltas=d, step=2 + reps, **kw)
-        reps += 1
+    def oracle_on(arrs, tab):
+        co2_oracle.outer_step_f32(seg_off=tab, x=arrs[0], a=arrs[1], m=arrs[2], deltas=arrs[3:], **kw)
+
+    # ---- single thread, whole passes over the configuration
+    chunks = _segment_chunks(table, 1 << 26)
+    big = max(hi - lo for lo, hi, _ in chunks)
+    pinned = [torch.empty(big, dtype=torch.float32, pin_memory=True) for _ in dev_in]
+    spent, done, passes = 0.0, 0, 0
+    while passes < max_passes and spent < min_seconds:
+        for lo, hi, tab in chunks:
+            arrs = staged(pinned, lo, hi)
+            t0 = time.perf_counter()
+            oracle_on(arrs, tab)
+            spent += time.perf_counter() - t0
+            done += hi - lo
+        passes += 1
+    one = {"value": done / spent, "unit": "params/s", "cores": 1, "kind": "oracle", "sampled": False,
+           "sample": f"{passes} whole pass(es) over all {len(table) - 1} segments ({table[-1]} params, K={cfg.K}) "
+                     f"of the workload resident on the device, streamed in {len(chunks)} chunks of whole "
+                     f"segments; {spent:.1f} s inside the oracle, g++ -O2, 1 thread"}
+    del pinned
+
+    # ---- all cores: one unchanged oracle call per thread, each on its own chunk
+    cores = len(os.sched_getaffinity(0))
+    small = [c for c in _segment_chunks(table, 1 << 24) if c[1] - c[0] <= 1 << 24]
+    small.sort(key=lambda c: c[0] - c[1])
+    picked = small[:cores]
+    sets = []
+    for lo, hi, tab in picked:
+        pin = [torch.empty(hi - lo, dtype=torch.float32, pin_memory=True) for _ in dev_in]
+        sets.append((staged(pin, lo, hi), tab, pin))
+    best = None
+    for _ in range(3):
+        ths = [threading.Thread(target=oracle_on, args=(arrs, tab)) for arrs, tab, _ in sets]
+        t0 = time.perf_counter()
+        for th in ths:
+            th.start()
+        for th in ths:
+            th.join()
         el = time.perf_counter() - t0
-        if el > 12.0 or reps >= 64:
-            break
-    return {"value": n * reps / el, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(chosen)} whole segments ({n} of {table[-1]} params) of the same "
-                      f"workload, K={cfg.K}, {reps} outer steps in {el:.1f} s, g++ -O2, 1 thread"}
+        best = el if best is None else min(best, el)
+    total = sum(hi - lo for lo, hi, _ in picked)
+    many = {"value": total / best, "unit": "params/s", "cores": len(picked), "nproc": cores,
+            "kind": "oracle, one call per thread on disjoint chunks of whole segments (not a tuned baseline)",
+            "sampled": True,
+            "sample": f"{len(picked)} chunks ({total} of {table[-1]} params) run concurrently, best of 3"}
+    return one, many
 
 
 def overlap_bench(args):
@@ -251,14 +293,14 @@ def main():
         sizes = [4 * n] * 3 + [dbytes] * (K + 1)
         search = args.placement_candidates > 0
         placement = pl.choose_placement(sizes, probe if search else None, dev,
-                                        candidates=args.placement_candidates,
+                                        candidates=args.placement_candidates, probe_first=search,
                                         pieces=pl.DEFAULT_PIECES if args.piece_major else (),
                                         gaps=pl.DEFAULT_GAPS if search else (pl.PAGE,))
         a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"
 
-    def drift(t, bid):
-        sd = co2_inputs.seed_for(cfg.seed, bid)
+    def drift(t, bid, rnd=0):
+        sd = co2_inputs.seed_for(cfg.seed, bid, rnd)
         dst = x if t.dtype == torch.bfloat16 else t       # x doubles as fp32 scratch here
         if student:
             co2_inputs.fill_student_t_(dst, cfg.drift_scale, cfg.drift_nu, sd)
@@ -267,71 +309,84 @@ def main():
         if dst is not t:
             t.copy_(dst)
 
+    def live_inputs(t):
+        """What round t consumes besides the state the library carries: the K-1 peers'
+        pseudo-gradients of round t-1 and this worker's local parameters after its inner
+        loop (anchor + drift).  Drawn fresh for every round, outside every timed region."""
+        for k, pb in enumerate(peers):
+            drift(pb, 200 + k, t)
+        drift(x, 100, t)
+        x.add_(a)
+
     co2_inputs.fill_normal_(a, cfg.param_std, co2_inputs.seed_for(cfg.seed, 1))
     co2_inputs.fill_normal_(m, cfg.momentum_std, co2_inputs.seed_for(cfg.seed, 2))
-    drift(own[1], 99)
-    for k, pb in enumerate(peers):
-        drift(pb, 200 + k)
-    drift(x, 100); x.add_(a)                                # local params = anchor + drift
+    drift(own[1], 99)                                       # own pseudo-gradient of the round before round 1
     torch.cuda.synchronize()
 
     step_no = [1]
     bufs = (a, m, x, own, peers)
-
-    def one_step(ev=None):
-        launch(bufs, step_no[0], ev)
-        step_no[0] += 1
-
     warmup = max(args.warmup, 2 if carried else 0)   # carried sums exist from round 2 on
     for _ in range(warmup):
-        one_step()
+        live_inputs(step_no[0])
+        launch(bufs, step_no[0])
+        step_no[0] += 1
     torch.cuda.synchronize()
 
-    events = [(co2.HipEvent(), co2.HipEvent()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(events[i])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    ms_per_step = elapsed * 1e3 / args.steps
-    launch_mode = "eager"
+    # ---- timed rounds: per-round HIP events on the launch stream around the whole
+    # step (all its kernels) and, inside the library, around the sweep kernel.
+    step_ev = [(co2.HipEvent(), co2.HipEvent()) for _ in range(args.steps)]
+    sweep_ev = [(co2.HipEvent(), co2.HipEvent()) for _ in range(args.steps)]
+    clipped = torch.zeros(S, dtype=torch.int64, device=dev)
+    lam_hist, graphs = [], {}
     if args.hip_graph:
-        # two rounds = one period of the delta_out ping-pong; step parity continues from the eager loop
-        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
-        t_cap = step_no[0] + (step_no[0] % 2)               # even round first
-        with torch.cuda.graph(graph, stream=side):
-            capturing = torch.cuda.current_stream().cuda_stream
-            launch(bufs, t_cap, on=capturing)
-            launch(bufs, t_cap + 1, on=capturing)
-        if step_no[0] % 2:
-            one_step()                                      # bring the ping-pong to an even round
-        replays = max(1, args.steps // 2)
-        graph.replay()
+        # one graph per half of the delta_out ping-pong; inputs are refreshed between replays
+        side = torch.cuda.Stream()
+        for par in (0, 1):
+            graphs[par] = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graphs[par], stream=side):
+                launch(bufs, 2 + par, on=torch.cuda.current_stream().cuda_stream)   # any round >= 2 of that parity
+    wall0 = time.perf_counter()
+    for i in range(args.steps):
+        t = step_no[0]
+        live_inputs(t)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(replays):
-            graph.replay()
+        last = i == args.steps - 1
+        step_ev[i][0].record(stream)
+        if graphs:
+            graphs[t % 2].replay()
+        else:
+            launch(bufs, t, sweep_ev[i], clipped if last else None)
+        step_ev[i][1].record(stream)
+        lam_hist.append(lam.clone())
+        step_no[0] += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+
+    import statistics
+    step_ms = [b.elapsed_ms(e) for b, e in step_ev]
+    ms_per_step = statistics.median(step_ms)
+    launch_mode = "hip graph replays (one graph per round parity)" if graphs else "eager"
+    if graphs:
+        # the sweep's own events cannot be recorded inside a captured launch: time a few eager rounds for the roofline
+        sweep_ev = sweep_ev[:3]
+        for i in range(3):
+            live_inputs(step_no[0])
+            launch(bufs, step_no[0], sweep_ev[i], clipped if i == 2 else None)
+            step_no[0] += 1
         torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / (2 * replays)
-        launch_mode = f"hip graph of 2 rounds, {replays} replays (eager: {elapsed * 1e3 / args.steps:.4f} ms/step)"
-        del graph
-    sweep_ms = sum(b.elapsed_ms(e) for b, e in events) / args.steps
+        graphs.clear()
+    sweep_times = [b.elapsed_ms(e) for b, e in sweep_ev]
+    sweep_ms = sum(sweep_times) / len(sweep_times)
     per_elem = (26 + 2 * K) if bf16 else (28 + 4 * K)   # algorithmic bytes per coordinate, one sweep
     sweep_bytes = per_elem * n
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
-
-    # ---- one more step, untimed, that also counts the coordinates the clip changed
-    clipped = torch.zeros(S, dtype=torch.int64, device=dev)
-    launch(bufs, step_no[0], None, clipped)
-    step_no[0] += 1
-    torch.cuda.synchronize()
+    lam_all = torch.stack(lam_hist)
+    lam_min, lam_max = float(lam_all.min()), float(lam_all.max())
     clipped_count = int(clipped.sum().item())
 
     # ---- yardstick: plain copy kernel over one buffer pair (8 B/element)
     cb, ce = co2.HipEvent(), co2.HipEvent()
-    co2.co2_copy_f32(a, x, n, stream=stream)
+    co2.co2_copy_f32(a, x, n, stream=stream)               # x is redrawn before its next use
     cb.record(stream)
     for _ in range(5):
         co2.co2_copy_f32(a, x, n, stream=stream)
@@ -339,6 +394,7 @@ def main():
     ce.synchronize()
     copy_gbps = 8 * n * 5 / (cb.elapsed_ms(ce) * 1e-3) / 1e9
 
+    traffic_key = (cfg.name, args.deltas, K)
     out = {
         "metric": "outer-step params/sec",
         "value": n / (ms_per_step * 1e-3),
@@ -350,26 +406,36 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
                                f"c={cfg.c}", "form": args.form, "deltas": args.deltas, "launch": launch_mode,
+                   "inputs": "local params and the K-1 peers' pseudo-gradients redrawn before every round, "
+                             "untimed; the worker's own pseudo-gradient is the previous round's delta_out",
+                   "timing": {"per": "round, HIP events on the launch stream around all kernels of the step",
+                              "median_ms": ms_per_step, "min_ms": min(step_ms), "max_ms": max(step_ms),
+                              "mean_ms": sum(step_ms) / len(step_ms),
+                              "wall_s_including_input_generation": wall},
+                   "lambda_min": lam_min, "lambda_max": lam_max,
+                   "clipped_coordinates_last_timed_step": clipped_count,
                    "placement": ("separate allocations" if placement is None else
                                  placement.report() if args.placement_candidates > 0 else
                                  "first allocation"),
-                   "clipped_coordinates_in_one_step": clipped_count,
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.deltas, K)),   # the sweep's, either form
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(traffic_key, (None, None))[0],
+                     "traffic_source": MEASURED_TRAFFIC_BYTES.get(traffic_key, (None, None))[1],
                      "kernel": "fused_sweep", "kernel_ms": sweep_ms,
+                     "kernel_ms_min": min(sweep_times), "kernel_ms_max": max(sweep_times),
                      "algorithmic_bytes": sweep_bytes, "copy_kernel_gbps": copy_gbps},
     }
+    if not args.no_cpu_baseline and not bf16:
+        t = step_no[0]
+        live_inputs(t)
+        torch.cuda.synchronize()
+        out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu_baseline(cfg, table, bufs, t)
     del a, m, x, own, peers, bufs
     torch.cuda.synchronize()
     if placement is not None:
         placement.release()
-    del placement
-    torch.cuda.empty_cache()
-    if not args.no_cpu_baseline and not bf16:
-        out["cpu_baseline"] = cpu_baseline(cfg, table, args.cpu_sample_elems, dev)
     print(json.dumps(out))
 
 

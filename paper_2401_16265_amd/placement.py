@@ -100,6 +100,7 @@ class Placement:
     gap: int = PAGE                      # arena: bytes between consecutive buffers
     piece_bytes: int = 0                 # piece-major: requested piece size
     compacted_bytes: int = 0             # what compact_device_memory took before the search
+    first_ms: Optional[float] = None     # probe of a plain allocation made BEFORE compaction and search
     pieces_ms: dict = field(default_factory=dict)                 # piece size -> probe ms (or error text)
     arenas_ms: List[List[float]] = field(default_factory=list)    # [candidate][gap index]
     gaps: Tuple[int, ...] = ()
@@ -107,7 +108,11 @@ class Placement:
     def report(self) -> dict:
         chosen = (f"piece-major, {self.piece_bytes >> 20} MiB pieces" if self.kind == "piece-major"
                   else f"arena, gap {self.gap} B")
-        return {"compacted_gib": round(self.compacted_bytes / 2**30, 1),
+        flat = [t for row in self.arenas_ms for t in row] + [v for v in self.pieces_ms.values()
+                                                              if isinstance(v, float)]
+        return {"first_allocation_ms": None if self.first_ms is None else round(self.first_ms, 3),
+                "worst_candidate_ms": round(max(flat), 3) if flat else None,
+                "compacted_gib": round(self.compacted_bytes / 2**30, 1),
                 "piece_major_ms": {f"{k >> 20} MiB": (round(v, 3) if isinstance(v, float) else v)
                                    for k, v in self.pieces_ms.items()},
                 "arenas_ms": [[round(t, 3) for t in row] for row in self.arenas_ms],
@@ -124,7 +129,8 @@ class Placement:
 def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.Tensor]], float]],
                      device, candidates: int = 4, gaps: Sequence[int] = DEFAULT_GAPS,
                      pieces: Sequence[int] = (), reserve_bytes: int = 4 << 30,
-                     spacer_bytes: int = 192 << 20, buffer_set=None, compact: bool = True) -> Placement:
+                     spacer_bytes: int = 192 << 20, buffer_set=None, compact: bool = True,
+                     probe_first: bool = False) -> Placement:
     """Allocate buffers of `sizes` bytes where `probe` runs fastest.
 
     With `probe` None this is one plain allocation with the first gap.  Otherwise:
@@ -138,7 +144,10 @@ def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.
     every candidate is backed by different physical pages; at most three
     candidates are alive at once, fewer if device memory, less `reserve_bytes`,
     does not hold them.  The kept buffers contain whatever the probe left in them:
-    initialise them afterwards.
+    initialise them afterwards.  `probe_first`: before anything else, also time the
+    probe on one plain allocation exactly as the device hands it out (no compaction,
+    first gap) and free it again -- the figure a caller gets who does none of this
+    (reported as `first_ms`).
     """
     gaps = tuple(gaps)
     if not gaps:
@@ -157,6 +166,14 @@ def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.
         if owner is not None and hasattr(owner, "close"):
             owner.close()
 
+    first_ms = None
+    if probe_first:
+        arena = torch.empty(total, dtype=torch.uint8, device=device)
+        arena.zero_()
+        first_ms = float(probe(carve(arena, sizes, gaps[0])))
+        del arena
+        if on_gpu:
+            torch.cuda.empty_cache()
     compacted = compact_device_memory(device) if compact else 0
     best = None          # (ms, Placement)
     loser = None         # the latest plain allocation that lost, kept until the next one exists
@@ -215,4 +232,5 @@ def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.
     torch.cuda.empty_cache()
     kept.pieces_ms, kept.arenas_ms, kept.gaps = pieces_ms, arenas_ms, gaps
     kept.compacted_bytes = compacted
+    kept.first_ms = first_ms
     return kept

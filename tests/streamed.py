@@ -1,0 +1,299 @@
+"""Whole-vector parity at the workloads' real sizes: the HIP library against the
+CPU oracle on EVERY element, streamed in chunks of whole segments.
+
+The device holds the full workload.  The oracle side holds its own full state
+(anchor, momentum, own pseudo-gradient) in host memory and advances it chunk by
+chunk: segments are independent in the update, so a group of whole segments with
+a re-based segment table is itself a valid, smaller problem for the oracle, and
+several such groups can be handed to the (single-threaded, unchanged) oracle
+from several host threads at once.  Per chunk a worker thread
+
+  1. copies the chunk of every INPUT both sides consume (the local drift, the
+     peers' pseudo-gradients -- all drawn by co2_inputs on the device) to pinned
+     host memory,
+  2. runs the oracle on it, in place on the oracle's own state,
+  3. copies the chunk of every OUTPUT the device produced and compares it with
+     the oracle's, element by element (bit equality first; where bits differ,
+     the 1e-5 relative bar).
+
+Data only ever flows device -> host as inputs or for comparison; nothing the HIP
+library computed is fed to the oracle.
+"""
+from __future__ import annotations
+
+import queue
+import threading
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+import co2_inputs
+import paper_2401_16265_amd as co2
+from harness import HP, REL_TOL, rel_err
+from oracle import co2_oracle
+
+
+@dataclass
+class Chunk:
+    i0: int                          # compact segment range [i0, i1)
+    i1: int
+    c0: int                          # compact element range [c0, c1)
+    c1: int
+    runs: List[Tuple[int, int]]      # device element ranges, in order, that make up [c0, c1)
+    table: np.ndarray                # segment table of the chunk, re-based to 0
+
+    @property
+    def elems(self) -> int:
+        return self.c1 - self.c0
+
+
+class SegmentChunks:
+    """A sample of whole segments (default: all of them) of a device-sized table,
+    packed into a compact index space and cut into chunks of consecutive sampled
+    segments of at most `chunk_elems` elements (a larger segment is a chunk of its
+    own)."""
+
+    def __init__(self, table: Sequence[int], sample: Optional[Sequence[int]], chunk_elems: int):
+        self.table = [int(o) for o in table]
+        S = len(self.table) - 1
+        self.sample = list(range(S)) if sample is None else sorted(set(sample))
+        sizes = [self.table[s + 1] - self.table[s] for s in self.sample]
+        self.otable = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        self.n = int(self.otable[-1])
+        self.chunks: List[Chunk] = []
+        i = 0
+        while i < len(self.sample):
+            j, total = i, 0
+            while j < len(self.sample) and (j == i or total + sizes[j] <= chunk_elems):
+                total += sizes[j]
+                j += 1
+            runs: List[Tuple[int, int]] = []
+            for k in range(i, j):
+                lo, hi = self.table[self.sample[k]], self.table[self.sample[k] + 1]
+                if hi == lo:
+                    continue
+                if runs and runs[-1][1] == lo:
+                    runs[-1] = (runs[-1][0], hi)
+                else:
+                    runs.append((lo, hi))
+            c0, c1 = int(self.otable[i]), int(self.otable[j])
+            self.chunks.append(Chunk(i, j, c0, c1, runs, (self.otable[i:j + 1] - c0).astype(np.int64)))
+            i = j
+        self.max_chunk = max(c.elems for c in self.chunks)
+        # largest first: the thread pool then balances better
+        self.order = sorted(range(len(self.chunks)), key=lambda q: -self.chunks[q].elems)
+
+
+# Pinned staging memory is slow to obtain and identical for every test of a
+# process: one pool, grown on demand, handed out as sets of equally sized buffers.
+_POOL = {"sets": [], "nbuf": 0, "nbytes": 0}
+_POOL_LOCK = threading.Lock()
+
+
+def staging_sets(nsets: int, nbuf: int, nbytes: int) -> "queue.Queue":
+    with _POOL_LOCK:
+        if _POOL["nbuf"] < nbuf or _POOL["nbytes"] < nbytes or len(_POOL["sets"]) < nsets:
+            nb = max(nbuf, _POOL["nbuf"])
+            by = max(nbytes, _POOL["nbytes"])
+            ns = max(nsets, len(_POOL["sets"]))
+            _POOL["sets"] = []                 # drop the old blocks before taking larger ones
+            _POOL["sets"] = [[torch.empty(by, dtype=torch.uint8, pin_memory=True) for _ in range(nb)]
+                             for _ in range(ns)]
+            _POOL["nbuf"], _POOL["nbytes"] = nb, by
+        q: "queue.Queue" = queue.Queue()
+        for s in _POOL["sets"][:nsets]:
+            q.put(s)
+        return q
+
+
+_TLS = threading.local()
+
+
+def _copy_stream() -> torch.cuda.Stream:
+    if not hasattr(_TLS, "stream"):
+        _TLS.stream = torch.cuda.Stream()      # default priority
+    return _TLS.stream
+
+
+def stage(dev_buf: torch.Tensor, chunk: Chunk, pinned: torch.Tensor, ready: torch.cuda.Event) -> np.ndarray:
+    """Chunk of a device buffer -> numpy view of `pinned` (bf16 buffers come back
+    as their uint16 bit patterns).  Waits for `ready` on the device first."""
+    if dev_buf.dtype == torch.bfloat16:
+        dev_buf = dev_buf.view(torch.int16)
+    host = pinned.view(dev_buf.dtype)[:chunk.elems]
+    s = _copy_stream()
+    with torch.cuda.stream(s):
+        s.wait_event(ready)
+        off = 0
+        for lo, hi in chunk.runs:
+            host[off:off + hi - lo].copy_(dev_buf[lo:hi], non_blocking=True)
+            off += hi - lo
+    s.synchronize()
+    out = host.numpy()
+    return out.view(np.uint16) if out.dtype == np.int16 else out
+
+
+def for_each_chunk(chunks: SegmentChunks, fn, workers: int):
+    """fn(chunk) for every chunk on a pool of host threads; the first exception wins."""
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        futs = [ex.submit(fn, chunks.chunks[q]) for q in chunks.order]
+        for f in futs:
+            f.result()
+
+
+def same_or_close(got: np.ndarray, want: np.ndarray, what: str, stats: dict):
+    """Bit equality, else the 1e-5 relative bar element by element."""
+    if np.array_equal(got, want):
+        return
+    stats["bit_exact"] = False
+    e = rel_err(got, want)
+    stats["worst"] = max(stats.get("worst", 0.0), e)
+    assert e <= REL_TOL, f"{what}: max relative error {e:.3e} > {REL_TOL:g}"
+
+
+class StreamedOuterStepHarness:
+    """co2_outer_step / co2_outer_step_bf16 over consecutive rounds, compared with
+    the oracle on every element of the sampled segments (default: all segments)."""
+
+    def __init__(self, table: Sequence[int], hp: HP, device, seed: int = 0,
+                 sample: Optional[Sequence[int]] = None, drift: str = "normal",
+                 drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
+                 momentum_std: float = 0.02, start_step: int = 1, bf16: bool = False,
+                 chunk_elems: int = 1 << 26, workers: int = 8):
+        self.table = [int(o) for o in table]
+        self.n, self.S = self.table[-1], len(self.table) - 1
+        self.hp, self.dev, self.seed, self.bf16 = hp, device, seed, bf16
+        self.drift, self.drift_scale, self.drift_nu = drift, drift_scale, drift_nu
+        self.workers = workers
+        co2_oracle.build()                               # before any worker thread needs it
+        co2_oracle.sqnorms(np.zeros(1, np.float32), [0, 1])
+        self.seg = co2.SegmentTable(self.table, device)
+        self.ch = SegmentChunks(self.table, sample, chunk_elems)
+        n, K = self.n, hp.K
+        f32 = dict(dtype=torch.float32, device=device)
+        dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+        self.x, self.a, self.m = (torch.empty(n, **f32) for _ in range(3))
+        self.noise = torch.empty(n, **f32)          # this round's local drift (an input of both sides)
+        self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]
+        self.peers = [torch.zeros(n, **dd) for _ in range(K - 1)]
+        self.lam = torch.empty(self.S, **f32)
+        self.clipped = torch.full((self.S,), -1, dtype=torch.int64, device=device)
+        self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
+        co2_inputs.fill_normal_(self.a, param_std, co2_inputs.seed_for(seed, 1))
+        if momentum_std > 0:
+            co2_inputs.fill_normal_(self.m, momentum_std, co2_inputs.seed_for(seed, 2))
+        else:
+            self.m.zero_()
+        self.t = start_step
+        # staging: the K-1 peers + the drift as inputs; outputs reuse the same buffers afterwards
+        self.sets = staging_sets(workers, max(K, 4), 4 * self.ch.max_chunk)
+        # ---- oracle state over the compact index space
+        nc = self.ch.n
+        self.o_a = np.empty(nc, dtype=np.float32)
+        self.o_m = np.empty(nc, dtype=np.float32)
+        self.o_own = np.zeros(nc, dtype=np.uint16 if bf16 else np.float32)
+        if start_step >= 1:
+            # no earlier round produced the worker's own previous pseudo-gradient: drawn like a peer's
+            self._fill_drift(self.own[start_step % 2], 99)
+        ready = torch.cuda.Event()
+        ready.record()
+
+        def init(c: Chunk):
+            st = self.sets.get()
+            try:
+                self.o_a[c.c0:c.c1] = stage(self.a, c, st[0], ready)
+                self.o_m[c.c0:c.c1] = stage(self.m, c, st[1], ready)
+                if start_step >= 1:
+                    self.o_own[c.c0:c.c1] = stage(self.own[start_step % 2], c, st[2], ready)
+            finally:
+                self.sets.put(st)
+        for_each_chunk(self.ch, init, workers)
+
+    def _fill_drift(self, t: torch.Tensor, buffer_id: int):
+        sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)
+        dst = self.noise if t.dtype == torch.bfloat16 else t
+        if self.drift == "student_t":
+            co2_inputs.fill_student_t_(dst, self.drift_scale, self.drift_nu, sd)
+        else:
+            co2_inputs.fill_normal_(dst, self.drift_scale, sd)
+        if dst is not t:
+            t.copy_(dst)                          # the sender's rounding to bf16 (input synthesis)
+
+    def step(self, flags: int = 0) -> dict:
+        """One outer round on both sides; every sampled element compared.  Returns
+        dict(bit_exact, worst, nclipped, lam_min, lam_max)."""
+        hp, t, K = self.hp, self.t, self.hp.K
+        cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]       # cur: deltas[0]; nxt: delta_out
+        if t >= 1:
+            for k, pbuf in enumerate(self.peers):               # before the drift: bf16 peers are drawn through `noise`
+                self._fill_drift(pbuf, 200 + k)
+        self._fill_drift(self.noise, 100)
+        torch.add(self.a, self.noise, out=self.x)               # inner loop stand-in
+        p = co2.make_params(self.seg, K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
+                            clipped_out=self.clipped)
+        entry = co2.co2_outer_step_bf16 if self.bf16 else co2.co2_outer_step
+        entry(p, self.x, self.a, self.a, self.m, [cur] + self.peers, nxt, None, self.lam, self.ws)
+        ready = torch.cuda.Event()
+        ready.record()
+        params_equal_anchor = torch.equal(self.x, self.a)       # both hold x_{t+1,0}
+
+        S_c = len(self.ch.sample)
+        o_lam = np.ones(S_c, dtype=np.float32)
+        o_clip = np.zeros(S_c, dtype=np.int64)
+        stats = {"bit_exact": True, "worst": 0.0}
+        lock = threading.Lock()
+        oracle_step = co2_oracle.outer_step_bf16 if self.bf16 else co2_oracle.outer_step_f32
+        phi32 = np.float32(hp.phi)
+
+        def work(c: Chunk):
+            st = self.sets.get()
+            try:
+                sl = slice(c.c0, c.c1)
+                o_x = self.o_a[sl] + stage(self.noise, c, st[0], ready)     # same fp32 add as on the device
+                o_d = None
+                if t >= 1:
+                    o_d = [self.o_own[sl]] + [stage(pb, c, st[1 + k], ready)
+                                              for k, pb in enumerate(self.peers)]
+                out = oracle_step(seg_off=c.table, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
+                                  tau=hp.tau, step=t, x=o_x, a=self.o_a[sl], m=self.o_m[sl], deltas=o_d)
+                self.o_own[sl] = out["dout"]
+                local = {"bit_exact": True, "worst": 0.0}
+                assert np.array_equal(o_x, self.o_a[sl]), "oracle: params and anchor must both hold x_{t+1,0}"
+                same_or_close(stage(self.a, c, st[0], ready), self.o_a[sl], "anchor", local)
+                same_or_close(stage(self.m, c, st[1], ready), self.o_m[sl], "momentum", local)
+                g_d = stage(nxt, c, st[2], ready)
+                if self.bf16:
+                    assert np.array_equal(g_d, out["dout"]), "delta_out (bf16 bit patterns) differs"
+                else:
+                    same_or_close(g_d, out["dout"], "delta_out", local)
+                o_lam[c.i0:c.i1] = out["lam"]
+                if t >= 1:
+                    om = self.o_m[sl]
+                    for i in range(c.i0, c.i1):
+                        lo, hi = int(c.table[i - c.i0]), int(c.table[i - c.i0 + 1])
+                        o_clip[i] = np.count_nonzero(np.abs(om[lo:hi]) > phi32)
+                    assert int(o_clip[c.i0:c.i1].sum()) == out["nclipped"]
+                with lock:
+                    stats["bit_exact"] &= local["bit_exact"]
+                    stats["worst"] = max(stats["worst"], local["worst"])
+            finally:
+                self.sets.put(st)
+
+        for_each_chunk(self.ch, work, self.workers)
+        torch.cuda.synchronize()
+        assert params_equal_anchor, "device: params and anchor must both hold x_{t+1,0}"
+        g_clip = self.clipped[self.ch.sample].cpu().numpy()
+        assert np.array_equal(g_clip, o_clip), "clipped-coordinate counts differ"
+        if t >= 1:
+            g_lam = self.lam[self.ch.sample].cpu().numpy()
+            e = rel_err(g_lam, o_lam)
+            assert e <= REL_TOL, f"Lambda: max relative error {e:.3e}"
+            stats["lambda_err"] = e
+        stats.update(nclipped=int(o_clip.sum()), lam_min=float(o_lam.min()), lam_max=float(o_lam.max()),
+                     elements=self.ch.n, segments=S_c)
+        self.o_lam = o_lam
+        self.t += 1
+        return stats

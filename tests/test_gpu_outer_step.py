@@ -17,6 +17,7 @@ import torch
 import co2_inputs
 import paper_2401_16265_amd as co2
 from harness import HP, OuterStepHarness, assert_close
+from streamed import StreamedOuterStepHarness
 
 pytestmark = pytest.mark.gpu
 INF = float("inf")
@@ -149,19 +150,21 @@ def test_bf16_deltas_edge_shapes(dev, name, K):
     run_steps(h, 3)
 
 
-def test_bf16_deltas_1p3b_sampled(dev):
-    """Headline-size buffers with bf16 pseudo-gradient transport (42 B/param)."""
+def test_bf16_deltas_1p3b_every_element(dev):
+    """Headline-size buffers with bf16 pseudo-gradient transport (42 B/param): every
+    element of every output and every Lambda against the oracle, three consecutive
+    rounds, the last one in the carried (single-pass) form."""
     cfg = co2_inputs.CONFIGS["1p3b"]
     table = co2_inputs.config_table(cfg)
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
-    sample = [1, 2, 3, 4, 5, 10, 11, 150, 151, 286, 287, 288, 289, 290, 291]
-    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift="student_t",
-                         drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
-                         momentum_std=cfg.momentum_std, start_step=1, bf16=True)
-    for t in range(3):
-        print(f"  1p3b bf16 step {h.t}", flush=True)
-        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0)
-    print("   ", res, flush=True)
+    h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed, drift="student_t",
+                                 drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
+                                 momentum_std=cfg.momentum_std, start_step=1, bf16=True)
+    assert h.ch.n == 1_343_868_928
+    for i in range(3):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 2 else 0)
+        print(f"  1p3b bf16 step {h.t - 1}: {res}", flush=True)
+    assert res["lam_max"] > 1.0
 
 
 def test_carried_norms_equal_two_pass(dev):
@@ -272,41 +275,44 @@ def test_pseudo_grad_norms(dev, oracle):
 
 # ------------------------------------------------------------------ config 2, full size
 def test_gpt2_small_ten_steps(dev):
+    """All 124 439 808 elements and all 148 Lambda, ten consecutive rounds."""
     cfg = co2_inputs.CONFIGS["gpt2s"]
     table = co2_inputs.config_table(cfg)
     assert table[-1] == 124_439_808 and len(table) - 1 == 148
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
-    # every segment of layers 0 and 11, both embeddings and the final norm
-    sample = [0, 1] + list(range(2, 14)) + list(range(134, 148))
-    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift_scale=cfg.drift_scale,
-                         momentum_std=cfg.momentum_std, start_step=1)
-    res = run_steps(h, cfg.steps)
-    print("gpt2s last step:", res[-1])
+    h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed, drift_scale=cfg.drift_scale,
+                                 momentum_std=cfg.momentum_std, start_step=1, chunk_elems=1 << 24)
+    assert cfg.steps == 10 and h.ch.n == table[-1]
+    for i in range(cfg.steps):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 1 else 0)
+        print(f"  gpt2s step {h.t - 1}: {res}", flush=True)
 
 
 # ------------------------------------------------------------------ config 3, headline size
-def test_1p3b_headline_size_sampled(dev):
-    """Full 1.34B-parameter buffers, K=8, Student-t drift, in the launch
-    configuration the bench times (carried norms after the first two rounds);
-    outputs checked on a sample of whole segments that includes the largest
-    (131M elements), the smallest, and segments from the first/middle/last layers."""
+def test_1p3b_headline_every_element_twenty_steps(dev):
+    """The headline workload as stated: 1 343 868 928 parameters in 292 segments,
+    K=8, Student-t drift, 20 consecutive outer rounds in the launch configuration
+    the bench times (carried norms after the first two rounds).  EVERY element of
+    params, anchor, momentum and delta_out and every Lambda and clipped count of
+    every round is compared with the oracle, which carries its own full state."""
     cfg = co2_inputs.CONFIGS["1p3b"]
     table = co2_inputs.config_table(cfg)
-    assert table[-1] == 1_343_868_928 and len(table) - 1 == 292
+    assert table[-1] == 1_343_868_928 and len(table) - 1 == 292 and cfg.steps == 20
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
-    sample = [0, 1, 2, 3, 4, 5, 10, 11, 150, 151, 152, 286, 287, 288, 289, 290, 291]
-    h = OuterStepHarness(table, hp, dev, seed=cfg.seed, sample=sample, drift="student_t",
-                         drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
-                         momentum_std=cfg.momentum_std, start_step=1)
-    for t in range(4):
-        flags = co2.CO2_FLAG_CARRIED_NORMS if t >= 2 else 0
-        print(f"  1p3b step {h.t} flags={flags}", flush=True)
-        res = h.step(flags=flags, full_check=(t == 3))
-        print("   ", res, "nclipped(sample)=", h.last["nclipped"], flush=True)
-    lam = h.lam.cpu().numpy()
-    assert np.all(lam >= 1.0) and np.all(np.isfinite(lam))
-    # Norms of ALL 292 segments at full size: the norms entry point against the
-    # oracle's ascending fp64 sums over the whole momentum and own-delta buffers.
+    h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed, drift="student_t",
+                                 drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
+                                 momentum_std=cfg.momentum_std, start_step=1)
+    assert h.ch.n == table[-1] and len(h.ch.sample) == 292
+    clipped_steps, lam_max = 0, 1.0
+    for i in range(cfg.steps):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 2 else 0)
+        print(f"  1p3b step {h.t - 1}: {res}", flush=True)
+        clipped_steps += res["nclipped"] > 0
+        lam_max = max(lam_max, res["lam_max"])
+    assert clipped_steps > 0, "the heavy-tailed drift should trigger the clamp on some rounds"
+    assert lam_max > 1.0
+    # Norms of ALL 292 segments at full size through the norms entry point, against the
+    # oracle's ascending fp64 sums over the oracle's own momentum and pseudo-gradient.
     from oracle import co2_oracle
     own = h.own[h.t % 2]
     out = torch.empty(2, h.S, dtype=torch.float64, device=dev)
@@ -317,8 +323,8 @@ def test_1p3b_headline_size_sampled(dev):
     # The oracle adds up to 1.3e8 non-negative terms one after the other, so its own sum
     # is only good to about N * 2^-53 ~ 1e-8 relative (the device's tree order is tighter);
     # 1e-9 is four orders inside the 1e-5 bar.
-    assert_close(got[0], co2_oracle.sqnorms(own.cpu().numpy(), table), "sum of d0^2, all segments", tol=1e-9)
-    assert_close(got[1], co2_oracle.sqnorms(h.m.cpu().numpy(), table, phi=hp.phi),
+    assert_close(got[0], co2_oracle.sqnorms(h.o_own, table), "sum of d0^2, all segments", tol=1e-9)
+    assert_close(got[1], co2_oracle.sqnorms(h.o_m, table, phi=hp.phi),
                  "sum of Clip(m)^2, all segments", tol=1e-9)
 
 
@@ -341,15 +347,16 @@ def test_flat_index_beyond_2_to_31(dev):
 # ------------------------------------------------------------------ config 4, ZeRO-style shard
 @pytest.mark.parametrize("rank", [1, 0])
 def test_7b_shard_partial_segments(dev, rank):
+    """One 1/16 slice of the 7B table (first and last segments are partial tensors):
+    all 421 150 976 elements, 20 consecutive rounds."""
     cfg = co2_inputs.CONFIGS["7b_shard"]
     table = co2_inputs.config_table(cfg, rank=rank)
-    assert table[-1] == 421_150_976
+    assert table[-1] == 421_150_976 and cfg.steps == 20
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
-    S = len(table) - 1
-    sample = sorted({0, 1, 2, S // 2, S - 2, S - 1})       # first and last are partial tensors
-    h = OuterStepHarness(table, hp, dev, seed=cfg.seed + rank, sample=sample,
-                         drift_scale=cfg.drift_scale, momentum_std=cfg.momentum_std, start_step=1)
-    for t in range(3):
-        print(f"  7b shard rank {rank} step {h.t}", flush=True)
-        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if t >= 1 else 0, full_check=(t == 2))
-    print("7b shard:", res)
+    h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed + rank, drift_scale=cfg.drift_scale,
+                                 momentum_std=cfg.momentum_std, start_step=1, chunk_elems=1 << 25)
+    assert h.ch.n == table[-1]
+    for i in range(cfg.steps):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 1 else 0)
+        print(f"  7b shard rank {rank} step {h.t - 1}: {res}", flush=True)
+    assert res["lam_max"] > 1.0

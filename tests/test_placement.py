@@ -55,7 +55,8 @@ def test_fastest_arena_and_gap_is_kept():
     assert len(seen) == 9
     assert p.views[0].data_ptr() == seen[4][0]                   # candidate 1's memory
     assert p.views[1].data_ptr() - p.views[0].data_ptr() == 8192 + 8192
-    assert p.report() == {"compacted_gib": 0.0, "piece_major_ms": {},
+    assert p.report() == {"first_allocation_ms": None, "worst_candidate_ms": 9.0,
+                          "compacted_gib": 0.0, "piece_major_ms": {},
                           "arenas_ms": [[5.0, 4.0, 6.0], [3.5, 2.5, 9.0], [7.0, 7.0, 7.0]],
                           "gaps_bytes": [4096, 8192, 12288], "chosen": "arena, gap 8192 B"}
     # the three candidates were distinct allocations held at the same time
@@ -116,3 +117,22 @@ def test_arena_beats_piece_major_and_failed_sets_are_reported():
 
 def test_compaction_is_a_no_op_off_the_gpu():
     assert pl.compact_device_memory("cpu") == 0
+
+
+def test_first_allocation_is_probed_before_the_search():
+    """probe_first: one plain allocation, first gap, timed before compaction and
+    search, reported beside the candidates."""
+    script = iter([8.5, 5.0, 4.0, 3.0, 6.0])
+    calls = []
+
+    def probe(views):
+        calls.append(views[1].data_ptr() - views[0].data_ptr())
+        return next(script)
+
+    p = pl.choose_placement([4096, 4096], probe, "cpu", candidates=2, gaps=(4096, 8192), pieces=(),
+                            probe_first=True)
+    assert calls[0] == 4096 + 4096                       # the first gap
+    assert len(calls) == 5
+    rep = p.report()
+    assert rep["first_allocation_ms"] == 8.5 and rep["worst_candidate_ms"] == 6.0
+    assert p.gap == 4096 and rep["arenas_ms"] == [[5.0, 4.0], [3.0, 6.0]]

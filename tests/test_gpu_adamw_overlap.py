@@ -178,12 +178,130 @@ def test_overlapped_rounds_tau_one(dev):
     run_rounds(dev, table, [0, 1, 2], K=2, tau=1, rounds=4, seed=5, phi=1.0)
 
 
+class StreamedOracleWorker:
+    """OracleWorker over EVERY segment of a large table: the oracle's own full state
+    on the host, advanced chunk by chunk (whole segments) on a pool of host threads,
+    inputs staged from the device through pinned memory (see streamed.py)."""
+
+    def __init__(self, table, K, tau, alpha, beta, phi, c, params_init, workers=8, chunk_elems=1 << 25):
+        import streamed
+        self.st = streamed
+        self.ch = streamed.SegmentChunks(table, None, chunk_elems)
+        self.K, self.tau, self.alpha, self.beta, self.phi, self.c = K, tau, alpha, beta, phi, c
+        self.workers = workers
+        n, S = self.ch.n, len(self.ch.sample)
+        self.sets = streamed.staging_sets(workers, tau + K - 1, 4 * self.ch.max_chunk)
+        co2_oracle.sqnorms(np.zeros(1, np.float32), [0, 1])
+        self.params = np.empty(n, np.float32)
+        ready = torch.cuda.Event(); ready.record()
+
+        def init(c):
+            st = self.sets.get()
+            try:
+                self.params[c.c0:c.c1] = streamed.stage(params_init, c, st[0], ready)
+            finally:
+                self.sets.put(st)
+        streamed.for_each_chunk(self.ch, init, workers)
+        self.exp_avg, self.exp_avg_sq = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        self.anchor = self.params.copy()
+        self.momentum = np.zeros(n, np.float32)
+        self.own_prev = np.zeros(n, np.float32)
+        self.fsn_prev = None
+        self.lam = np.ones(S, np.float32)
+        self.t, self.k = 0, 0
+
+    def round_and_compare(self, grads, peers, w, nxt_anchor):
+        """Advance the oracle by one round and compare every element of the device
+        worker `w` after the same round."""
+        stg, t, tau = self.st, self.t, self.tau
+        ready = torch.cuda.Event(); ready.record()
+        S = len(self.ch.sample)
+        fsn = np.zeros(S, np.float32)
+        lam = np.ones(S, np.float32)
+        stats = {"bit_exact": True, "worst": 0.0}
+        import threading
+        lock = threading.Lock()
+
+        def work(c):
+            st = self.sets.get()
+            try:
+                sl = slice(c.c0, c.c1)
+                g = [stg.stage(grads[k], c, st[k], ready) for k in range(tau)]
+                a = self.anchor[sl]
+                for k in range(tau):
+                    first, last = k == 0, k == tau - 1
+                    out = co2_oracle.adamw_f32(
+                        p_in=a if first else self.params[sl], p_out=self.params[sl], grad_bf16=g[k],
+                        exp_avg=self.exp_avg[sl], exp_avg_sq=self.exp_avg_sq[sl], k=self.k + k + 1,
+                        anchor=a if last else None, seg_off=c.table, want_step_sq=first, **HP)
+                    if first:
+                        fsn[c.i0:c.i1] = np.sqrt(out["step_sq"]).astype(np.float32)
+                    if last:
+                        own_cur = out["dout"]
+                d = None
+                if t >= 1:
+                    d = [self.own_prev[sl]] + [stg.stage(pb, c, st[tau + j], ready) for j, pb in enumerate(peers)]
+                a_next = np.empty_like(a)
+                lam[c.i0:c.i1] = co2_oracle.outer_step_f32(
+                    seg_off=c.table, alpha=self.alpha, beta=self.beta, phi=self.phi, c=self.c, tau=tau,
+                    step=t, x=None, a=a, a_out=a_next, m=self.momentum[sl], deltas=d,
+                    first_step_norm=None if self.fsn_prev is None else self.fsn_prev[c.i0:c.i1])["lam"]
+                self.anchor[sl] = a_next
+                self.own_prev[sl] = own_cur
+                local = {"bit_exact": True, "worst": 0.0}
+                for name, dev_buf, want in (("params", w.params, self.params), ("exp_avg", w.exp_avg, self.exp_avg),
+                                            ("exp_avg_sq", w.exp_avg_sq, self.exp_avg_sq),
+                                            ("momentum", w.momentum, self.momentum),
+                                            ("next anchor", nxt_anchor, self.anchor),
+                                            ("pseudo-gradient", w.own[t % 2], self.own_prev)):
+                    stg.same_or_close(stg.stage(dev_buf, c, st[0], ready), want[sl], name, local)
+                with lock:
+                    stats["bit_exact"] &= local["bit_exact"]
+                    stats["worst"] = max(stats["worst"], local["worst"])
+            finally:
+                self.sets.put(st)
+
+        stg.for_each_chunk(self.ch, work, self.workers)
+        if t >= 1:
+            assert_close(w.lam.cpu().numpy(), lam, "Lambda")
+        self.lam, self.fsn_prev = lam, fsn
+        self.k += tau
+        self.t += 1
+        return stats
+
+
 def test_overlapped_rounds_350m(dev):
-    """The overlapped-round workload at its real size (354.8M params, K=8, tau=4),
-    three rounds; oracle on a sample of whole segments."""
+    """The overlapped-round workload as stated: 354.8M params, K=8, tau=4 fused-AdamW
+    steps per round, 50 rounds.  Every round the overlapped schedule must equal the
+    serial order bit for bit, and EVERY element of params, both AdamW moments,
+    momentum, next anchor and pseudo-gradient must match the oracle, which carries
+    its own full state."""
     cfg = co2_inputs.CONFIGS["350m_overlap"]
     table = co2_inputs.config_table(cfg)
-    assert table[-1] == 354_823_168
-    S = len(table) - 1
-    sample = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, S - 2, S - 1]
-    run_rounds(dev, table, sample, K=cfg.K, tau=cfg.tau, rounds=3, seed=6, phi=cfg.phi)
+    assert table[-1] == 354_823_168 and cfg.steps == 50
+    seg = co2.SegmentTable(table, dev)
+    n, K, tau, seed = seg.n, cfg.K, cfg.tau, 6
+    f32 = dict(dtype=torch.float32, device=dev)
+    init = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(seed, 1))
+    mk = lambda: CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**HP), dev, init)  # noqa: E731
+    w_ov, w_se = mk(), mk()
+    ow = StreamedOracleWorker(table, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, init)
+    grads = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)]
+    lam_max = 1.0
+    for t in range(cfg.steps):
+        for k, g in enumerate(grads):
+            co2_inputs.fill_bf16_normal_(g, 1e-3, co2_inputs.seed_for(seed, 10 + k, t))
+        for j, pa in enumerate(w_ov.peers):
+            co2_inputs.fill_normal_(pa, 1e-3, co2_inputs.seed_for(seed, 200 + j, t))
+        w_se.peers = w_ov.peers                      # inputs only: both schedules read the same buffers
+        w_ov.round_overlapped(grads)
+        w_se.round_serial(grads)
+        torch.cuda.synchronize()
+        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam"):
+            assert torch.equal(getattr(w_ov, name), getattr(w_se, name)), f"{name}: overlap != serial"
+        for i in range(2):
+            assert torch.equal(w_ov.anchor[i], w_se.anchor[i]) and torch.equal(w_ov.own[i], w_se.own[i])
+        res = ow.round_and_compare(grads, w_ov.peers, w_ov, w_ov.anchor[(t + 1) % 2])
+        lam_max = max(lam_max, float(ow.lam.max()))
+        print(f"  350m round {t}: {res} lam_max={float(ow.lam.max()):.4f}", flush=True)
+    assert lam_max > 1.0

@@ -30,11 +30,12 @@
 //   * A coefficient c scales the ratio: Lambda = c*ratio + 1 (c = 1 is the
 //     paper, c = 0 is its "w/o penalty" ablation).  A zero denominator gives
 //     Lambda = 1.
-//   * Outer round t = 0 performs no momentum/iterate update (Section 3.1,
-//     "special case of first outer iteration"): x_{1,0} = x_{0,0}, m stays 0.
+//   * Outer round t = 0 skips the gap, momentum and iterate lines (Section
+//     3.1): x_{1,0} = x_{0,0}, m stays 0.
 //
-// parity pins: tests/test_oracle_*.py (hand-expanded example, closed forms,
-// invariants, library AdamW).  Nothing here is "parity unpinned".
+// parity pins: tests/test_oracle_*.py (hand-expanded examples, closed forms,
+// invariants, library momentum SGD / AdamW / lerp / clip_grad_norm_).  Nothing
+// here is "parity unpinned".
 
 #include <cmath>
 #include <cstddef>
@@ -236,6 +237,146 @@ int co2_oracle_outer_step_f64(int64_t n, int32_t S, const int64_t* seg_off,
       const double xn = aj - alpha * clip_coord<double>(mt, phi);
       m[j] = mt;
       if (x) x[j] = xn;
+      a_out[j] = xn;
+    }
+  }
+  return 0;
+}
+
+// ---------------------------------------------------------------------------
+// The family of local-update outer rules CO2 is built on or compared with,
+// stated in the buffers of the update above.  Three independent switches:
+//
+//   nonstale   The momentum line in the order of the method CO2 starts from
+//              (Section 3.2, the recursion m_{t+1} = beta*m_t + (x_{t,0} - x_{t,tau})
+//              written before the staleness is introduced): the mean is taken
+//              over THIS round's pseudo-gradients, i.e. the worker's own
+//              a - x formed in this call and the K-1 peers' in d[1..K-1]
+//              (d[0] is not read).  Round 0 is then an ordinary round.  With
+//              c = 0 and phi = +inf this is the slow-momentum update.
+//   pull_rho   Local parameters after the update.  1: they restart from the new
+//              outer iterate (Algorithm 1).  rho in (0,1): the anchor-model rule
+//              of the overlap variant of local SGD the paper discusses (its
+//              Discussions section): each worker keeps its own parameters and
+//              is only pulled towards the anchor, x <- x - rho*(x - x_{t+1,0}),
+//              while the anchor itself is updated as above.
+//   norm_clip  Clipping by rescaling instead of Section 3.3's coordinate-wise
+//              clamp (not in the paper; the usual alternative): per segment,
+//              Clip_norm(m, phi) = m * min(1, phi/||m||_s).  The numerator of
+//              Eq. 3 is then ||x_{t,0} - x_{t-1,0}||_s = alpha*min(||m_{t-1}||_s, phi).
+//
+// Every switch off reproduces co2_oracle_outer_step_f32 operation for operation.
+//   scale_out  optional S values: the factor min(1, phi/||m_t||_s) (1 without norm_clip)
+//   nclipped   coordinates with |m_t| > phi, or with norm_clip the number of
+//              coordinates that lie in a rescaled segment.
+int co2_oracle_outer_step_variant_f32(int64_t n, int32_t S, const int64_t* seg_off,
+                                      int32_t K, float alpha, float beta, float phi,
+                                      float c, int32_t tau, int64_t step,
+                                      int32_t nonstale, int32_t norm_clip, float pull_rho,
+                                      float* x, const float* a_in, float* a_out,
+                                      float* m, const float* const* d, float* dout,
+                                      const float* first_step_norm,
+                                      float* lambda_out, float* scale_out,
+                                      int64_t* nclipped) {
+  if (check_table(n, S, seg_off) || !a_in || !a_out || !m) return -1;
+  if ((x == nullptr) != (dout == nullptr)) return -1;
+  if (K < 1 || tau < 1 || !(phi > 0.0f) || step < 0) return -1;
+  if (!(pull_rho > 0.0f && pull_rho <= 1.0f)) return -1;
+  if ((nonstale || pull_rho != 1.0f) && !x) return -1;     // both need the local parameters
+  // No previous own pseudo-gradient is kept in the current-round order, so a
+  // penalty there needs the first-inner-step norms.
+  if (nonstale && c != 0.0f && !first_step_norm) return -1;
+  if (nclipped) *nclipped = 0;
+
+  if (step == 0 && !nonstale) {
+    // Stale order, first round: only the pseudo-gradient is formed.
+    for (int64_t j = 0; j < n; ++j) {
+      float aj = a_in[j];
+      if (x) { dout[j] = aj - x[j]; x[j] = aj; }
+      a_out[j] = aj;
+    }
+    for (int32_t s = 0; s < S; ++s) {
+      if (lambda_out) lambda_out[s] = 1.0f;
+      if (scale_out) scale_out[s] = 1.0f;
+    }
+    return 0;
+  }
+  if (!d && (K > 1 || !nonstale)) return -1;
+  for (int32_t k = nonstale ? 1 : 0; k < K; ++k) if (!d[k]) return -1;
+
+  const float rK = static_cast<float>(1.0 / static_cast<double>(K));
+
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t lo = seg_off[s], hi = seg_off[s + 1];
+
+    // Eq. 3 numerator: the displacement of the previous outer iterate.
+    double M2 = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      double v = static_cast<double>(norm_clip ? m[j] : clip_coord<float>(m[j], phi));
+      M2 += v * v;
+    }
+    double moved = std::sqrt(M2);                     // ||Clip(m_{t-1})||_s over alpha
+    if (norm_clip && moved > static_cast<double>(phi)) moved = static_cast<double>(phi);
+    // Eq. 3 denominator.
+    double T;
+    if (first_step_norm) {
+      T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
+    } else if (nonstale) {
+      T = 0.0;                                        // c == 0 here: Lambda stays 1
+    } else {
+      double P2 = 0.0;
+      for (int64_t j = lo; j < hi; ++j) {
+        double dv = static_cast<double>(d[0][j]);
+        P2 += dv * dv;
+      }
+      T = std::sqrt(P2);
+    }
+    double Lam = 1.0;
+    if (c != 0.0f && T != 0.0) {
+      Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * moved / T + 1.0;
+    }
+    const float inv = static_cast<float>(1.0 / Lam);
+    if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+
+    // Momentum line; the squared norm of m_t is needed before the iterate
+    // when clipping rescales.
+    double Q = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      const float aj = a_in[j];
+      if (x) dout[j] = aj - x[j];
+      float sum = nonstale ? dout[j] : d[0][j];
+      for (int32_t k = 1; k < K; ++k) sum = sum + d[k][j];
+      const float dbar = sum * rK;
+      const float bm = beta * m[j];
+      const float pen = dbar * inv;
+      const float mt = bm + pen;
+      m[j] = mt;
+      Q += static_cast<double>(mt) * static_cast<double>(mt);
+    }
+    float scale = 1.0f;
+    if (norm_clip) {
+      const double nrm = std::sqrt(Q);
+      if (nrm > static_cast<double>(phi)) scale = static_cast<float>(static_cast<double>(phi) / nrm);
+      if (nclipped && scale != 1.0f) *nclipped += hi - lo;
+    }
+    if (scale_out) scale_out[s] = scale;
+
+    // Outer-iterate line, then what the local parameters become.
+    for (int64_t j = lo; j < hi; ++j) {
+      const float mt = m[j];
+      const float cm = norm_clip ? mt * scale : clip_coord<float>(mt, phi);
+      const float stepv = alpha * cm;
+      const float xn = a_in[j] - stepv;
+      if (!norm_clip && nclipped && (mt > phi || mt < -phi)) ++*nclipped;
+      if (x) {
+        if (pull_rho == 1.0f) {
+          x[j] = xn;
+        } else {
+          const float gap = x[j] - xn;
+          const float pull = pull_rho * gap;
+          x[j] = x[j] - pull;
+        }
+      }
       a_out[j] = xn;
     }
   }

@@ -29,6 +29,7 @@ def build(force: bool = False) -> str:
 
 
 _ENTRY_POINTS = ("co2_oracle_sqnorms", "co2_oracle_outer_step_f32", "co2_oracle_outer_step_f64",
+                 "co2_oracle_outer_step_variant_f32",
                  "co2_oracle_outer_step_bf16", "co2_oracle_adamw_f32", "co2_oracle_adamw_f64")
 
 
@@ -161,6 +162,42 @@ def outer_step_f64(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
     if rc:
         raise ValueError("co2_oracle_outer_step_f64 rejected its arguments")
     return dict(dout=dout, lam=lam)
+
+
+def outer_step_variant_f32(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
+                           nonstale=False, norm_clip=False, pull_rho=1.0, a_out=None,
+                           first_step_norm=None):
+    """The outer update with the variant switches of co2_oracle_outer_step_variant_f32
+    (current-round mean, norm-rescale clip, anchor pull); in place like outer_step_f32.
+    With `nonstale`, deltas[0] is not read and may be None.
+    Returns dict(dout, lam, scale, nclipped)."""
+    lib = _load()
+    n = a.size
+    t, S = _table(n, seg_off)
+    if a_out is None:
+        a_out = a
+    dout = np.empty(n, dtype=np.float32) if x is not None else None
+    lam = np.empty(S, dtype=np.float32)
+    scale = np.empty(S, dtype=np.float32)
+    ncl = C.c_int64(0)
+    K = len(deltas) if deltas is not None else 1
+    dptr = None
+    if deltas is not None:
+        dptr = (C.c_void_p * K)()
+        for i, arr in enumerate(deltas):
+            dptr[i] = None if arr is None else _ptr(arr, np.float32).value
+    rc = lib.co2_oracle_outer_step_variant_f32(
+        C.c_int64(n), C.c_int32(S), _ptr(t, np.int64), C.c_int32(K),
+        C.c_float(alpha), C.c_float(beta), C.c_float(phi), C.c_float(c),
+        C.c_int32(tau), C.c_int64(step), C.c_int32(int(nonstale)), C.c_int32(int(norm_clip)),
+        C.c_float(pull_rho),
+        _ptr(x, np.float32), _ptr(a, np.float32), _ptr(a_out, np.float32),
+        _ptr(m, np.float32), dptr, _ptr(dout, np.float32),
+        _ptr(first_step_norm, np.float32), _ptr(lam, np.float32), _ptr(scale, np.float32),
+        C.byref(ncl))
+    if rc:
+        raise ValueError("co2_oracle_outer_step_variant_f32 rejected its arguments")
+    return dict(dout=dout, lam=lam, scale=scale, nclipped=ncl.value)
 
 
 def f32_to_bf16(values):

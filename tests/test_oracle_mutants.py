@@ -75,6 +75,30 @@ MUTANTS = [
     ("adamw_bf16_shift_wrong", "static_cast<uint32_t>(grad_bf16[j]) << 16;", "static_cast<uint32_t>(grad_bf16[j]) << 15;"),
     ("adamw_dout_sign", "if (dout) dout[j] = anchor[j] - p1;", "if (dout) dout[j] = p1 - anchor[j];"),
     ("adamw_step_norm_from_new_value", "const double df = static_cast<double>(p1 - p0);", "const double df = static_cast<double>(p1);"),
+    # ---- the variant switches (current-round mean, anchor pull, norm rescale)
+    ("variant_own_delta_left_out_of_current_mean", "float sum = nonstale ? dout[j] : d[0][j];",
+     "float sum = nonstale ? 0.0f : d[0][j];"),
+    ("variant_current_mean_reads_stale_own_delta", "float sum = nonstale ? dout[j] : d[0][j];",
+     "float sum = d[0][j];"),
+    ("variant_round_zero_skipped_in_current_order", "if (step == 0 && !nonstale) {", "if (step == 0) {"),
+    ("variant_numerator_not_capped_by_threshold",
+     "if (norm_clip && moved > static_cast<double>(phi)) moved = static_cast<double>(phi);", ""),
+    # (clamping the coordinates before that norm would be no mistake: min(||Clip(m)||, phi) == min(||m||, phi))
+    ("variant_scale_inverted", "scale = static_cast<float>(static_cast<double>(phi) / nrm);",
+     "scale = static_cast<float>(nrm / static_cast<double>(phi));"),
+    ("variant_scale_not_applied", "const float cm = norm_clip ? mt * scale : clip_coord<float>(mt, phi);",
+     "const float cm = norm_clip ? mt : clip_coord<float>(mt, phi);"),
+    ("variant_norm_of_new_momentum_not_squared", "Q += static_cast<double>(mt) * static_cast<double>(mt);",
+     "Q += static_cast<double>(mt);"),
+    ("variant_norm_taken_of_old_momentum", "Q += static_cast<double>(mt) * static_cast<double>(mt);",
+     "Q += static_cast<double>(bm) * static_cast<double>(bm);"),
+    ("variant_rescale_also_clamps", "const float cm = norm_clip ? mt * scale : clip_coord<float>(mt, phi);",
+     "const float cm = norm_clip ? clip_coord<float>(mt * scale, phi * 0.5f) : clip_coord<float>(mt, phi);"),
+    ("variant_pull_sign", "const float gap = x[j] - xn;", "const float gap = xn - x[j];"),
+    ("variant_pull_from_anchor", "x[j] = x[j] - pull;", "x[j] = xn - pull;"),
+    ("variant_pull_ignores_rho", "const float pull = pull_rho * gap;", "const float pull = gap;"),
+    ("variant_pull_moves_anchor_too", "          x[j] = x[j] - pull;\n        }\n      }\n      a_out[j] = xn;",
+     "          x[j] = x[j] - pull;\n        }\n      }\n      a_out[j] = x ? x[j] : xn;"),
     ("adamw_f64_first_moment", "const double m1 = beta1 * exp_avg[j] + (1.0 - beta1) * g;", "const double m1 = beta1 * exp_avg[j] + g;"),
 ]
 

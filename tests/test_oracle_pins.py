@@ -459,3 +459,227 @@ def test_bf16_step_equals_f32_step_on_widened_inputs(oracle, fsn):
         np.testing.assert_array_equal(o1["lam"], o2["lam"])
         assert o1["nclipped"] == o2["nclipped"]
         np.testing.assert_array_equal(o2["dout"], to_bits(o1["dout"]))
+
+
+# ---------------------------------------------------------------- variants of the outer rule
+# V0 hand-expanded example per switch (tests/golden)
+# V1 every switch off == outer_step_f32, bit for bit
+# V2 current-round mean: library momentum SGD from round 0; beta=0, alpha=1 == average of the
+#    workers' CURRENT parameters (Section 3.1's Local-SGD line)
+# V3 anchor pull: only the local parameters depend on rho; library lerp; rho=1/2 is the midpoint
+# V4 norm rescale: step norm <= alpha*phi; untouched segments == no clipping; library
+#    clip_grad_norm_; numerator of Eq. 3 == measured anchor displacement
+VGOLDEN = os.path.join(os.path.dirname(__file__), "golden", "outer_step_variants_worked_example.json")
+with open(VGOLDEN) as fh:
+    _V = json.load(fh)
+
+
+@pytest.mark.parametrize("case", _V["cases"], ids=[c["name"] for c in _V["cases"]])
+def test_v0_hand_expanded_variants(oracle, case):
+    c = _V["common"]
+    tol = 2e-7
+    a, x, m = f32(c["a"]), f32(c["x"]), f32(case["m"])
+    d0 = None if case["nonstale"] else f32(c["d0"])
+    if case["nonstale"]:
+        d_unused = f32([9.0, 9.0, 9.0, 9.0])       # must not be read
+        deltas = [d_unused, f32(c["d1"])]
+    else:
+        deltas = [d0, f32(c["d1"])]
+    fs = None if case["first_step_norm"] is None else f32(case["first_step_norm"])
+    out = oracle.outer_step_variant_f32(
+        seg_off=c["seg_off"], alpha=c["alpha"], beta=c["beta"],
+        phi=INF if case["phi"] is None else case["phi"], c=case["c"], tau=c["tau"],
+        step=case["step"], x=x, a=a, m=m, deltas=deltas, nonstale=case["nonstale"],
+        norm_clip=case["norm_clip"], pull_rho=case["pull_rho"], first_step_norm=fs)
+    np.testing.assert_allclose(out["dout"], c["dout"], rtol=0, atol=2.1 * tol)
+    np.testing.assert_allclose(out["lam"], case["lambda"], rtol=tol)
+    np.testing.assert_allclose(out["scale"], case["scale"], rtol=tol)
+    # in the current-round order a - x (a cancelling difference of values up to 2.1) enters m
+    np.testing.assert_allclose(m, case["m_new"], rtol=tol, atol=2.1 * tol if case["nonstale"] else 0)
+    np.testing.assert_allclose(a, case["anchor_new"], rtol=0, atol=2.1 * tol)
+    np.testing.assert_allclose(x, case["params_new"], rtol=0, atol=2.1 * tol)
+    assert out["nclipped"] == case["nclipped"]
+
+
+@pytest.mark.parametrize("use_fsn", [False, True])
+def test_v1_all_switches_off_is_the_base_update(oracle, use_fsn):
+    n, K = 3001, 5
+    table = [0, 0, 17, 1000, 1000, 2500, n]
+    a, x, m, d = rng_state(31, n, K)
+    fs = f32(np.abs(np.random.default_rng(5).normal(1e-3, 3e-4, len(table) - 1))) if use_fsn else None
+    kw = dict(seg_off=table, alpha=0.8, beta=0.9, phi=0.015, c=1.0, tau=3, first_step_norm=fs)
+    a1, x1, m1 = a.copy(), x.copy(), m.copy()
+    a2, x2, m2 = a.copy(), x.copy(), m.copy()
+    for step in (0, 1, 2):
+        o1 = oracle.outer_step_f32(x=x1, a=a1, m=m1, deltas=d if step else None, step=step, **kw)
+        o2 = oracle.outer_step_variant_f32(x=x2, a=a2, m=m2, deltas=d if step else None, step=step, **kw)
+        for u, v in ((a1, a2), (x1, x2), (m1, m2), (o1["dout"], o2["dout"]), (o1["lam"], o2["lam"])):
+            np.testing.assert_array_equal(u, v)
+        assert o1["nclipped"] == o2["nclipped"] and np.all(o2["scale"] == 1.0)
+        x1 += f32(np.random.default_rng(step).normal(0, 1e-3, n)); x2[:] = x1
+    # split form too
+    a3 = np.empty_like(a1)
+    a4 = np.empty_like(a1)
+    m3, m4 = m1.copy(), m1.copy()
+    oracle.outer_step_f32(x=None, a=a1, a_out=a3, m=m3, deltas=d, step=3, **kw)
+    oracle.outer_step_variant_f32(x=None, a=a2, a_out=a4, m=m4, deltas=d, step=3, **kw)
+    np.testing.assert_array_equal(a3, a4)
+    np.testing.assert_array_equal(m3, m4)
+
+
+def test_v2_current_round_mean_is_library_momentum_sgd_from_round_zero(oracle):
+    """Section 3.2's recursion before the staleness: with the current round's
+    pseudo-gradients, no penalty and no clipping the anchor follows the library's
+    momentum SGD on the mean pseudo-gradient, starting at round 0."""
+    n, K, alpha, beta, T = 211, 4, 0.6, 0.8, 5
+    r = np.random.default_rng(7)
+    a0 = f32(r.normal(0, 0.02, n))
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=alpha, momentum=beta)
+    a, m = a0.copy(), np.zeros(n, np.float32)
+    for t in range(T):
+        xs = [f32(a + r.normal(0, 1e-3, n)) for _ in range(K)]        # the K workers' local parameters
+        pg = [a.astype(np.float64) - xk for xk in xs]                 # their pseudo-gradients
+        p.grad = torch.tensor(np.mean(pg, axis=0))
+        opt.step()
+        x = xs[0].copy()
+        poison = np.full(n, 1e3, np.float32)                          # d[0] must not be read
+        out = oracle.outer_step_variant_f32(
+            seg_off=[0, 50, n], alpha=alpha, beta=beta, phi=INF, c=0.0, tau=2, step=t, x=x, a=a, m=m,
+            deltas=[poison] + [f32(a_prev - xk) for a_prev, xk in zip([a.copy()] * (K - 1), xs[1:])],
+            nonstale=True)
+        np.testing.assert_allclose(a, p.detach().numpy(), rtol=0, atol=3e-7 * (t + 1))
+        np.testing.assert_array_equal(x, a)
+        assert np.all(out["lam"] == 1.0) and out["nclipped"] == 0
+
+
+def test_v2_current_round_mean_averages_the_workers_parameters(oracle):
+    n, K = 97, 6
+    r = np.random.default_rng(8)
+    a0 = f32(r.normal(0, 0.02, n))
+    xs = [f32(a0 + r.normal(0, 1e-3, n)) for _ in range(K)]
+    a, m, x = a0.copy(), f32(r.normal(0, 1, n)), xs[0].copy()
+    oracle.outer_step_variant_f32(seg_off=[0, n], alpha=1.0, beta=0.0, phi=INF, c=0.0, tau=1, step=0,
+                                  x=x, a=a, m=m,
+                                  deltas=[np.full(n, 1e3, np.float32)] + [f32(a0 - xk) for xk in xs[1:]],
+                                  nonstale=True)                      # d[0] (poisoned) must not be read
+    np.testing.assert_allclose(a, np.mean(np.array(xs, dtype=np.float64), axis=0), rtol=0, atol=2e-8)
+
+
+def test_v2_penalty_in_current_round_order_needs_first_step_norms(oracle):
+    a, x, m, d = rng_state(9, 64, 2)
+    with pytest.raises(ValueError):
+        oracle.outer_step_variant_f32(seg_off=[0, 64], alpha=1.0, beta=0.9, phi=1.0, c=1.0, tau=2,
+                                      step=1, x=x, a=a, m=m, deltas=d, nonstale=True)
+
+
+@pytest.mark.parametrize("rho", [0.5, 0.25, 0.9])
+def test_v3_anchor_pull_moves_only_the_local_parameters(oracle, rho):
+    n, K = 2000, 3
+    table = [0, 300, 300, 1500, n]
+    a, x, m, d = rng_state(11, n, K)
+    kw = dict(seg_off=table, alpha=0.9, beta=0.9, phi=0.01, c=1.0, tau=4, step=2, deltas=d)
+    a1, x1, m1 = a.copy(), x.copy(), m.copy()
+    o1 = oracle.outer_step_f32(x=x1, a=a1, m=m1, **kw)
+    a2, x2, m2 = a.copy(), x.copy(), m.copy()
+    o2 = oracle.outer_step_variant_f32(x=x2, a=a2, m=m2, pull_rho=rho, **kw)
+    for u, v in ((a1, a2), (m1, m2), (o1["dout"], o2["dout"]), (o1["lam"], o2["lam"])):
+        np.testing.assert_array_equal(u, v)
+    # params = x - rho*(x - anchor') : the library's linear interpolation from x towards anchor'
+    want = torch.lerp(torch.tensor(x, dtype=torch.float64), torch.tensor(a2, dtype=torch.float64), rho).numpy()
+    np.testing.assert_allclose(x2, want, rtol=0, atol=1e-8)      # a few fp32 roundings at |x| ~ 0.05
+    if rho == 0.5:
+        np.testing.assert_allclose(x2, (x.astype(np.float64) + a2) / 2, rtol=0, atol=1e-8)
+    # what is left of the gap to the anchor
+    np.testing.assert_allclose(x2.astype(np.float64) - a2, (1 - rho) * (x.astype(np.float64) - a2),
+                               rtol=0, atol=1e-8)
+    assert not np.array_equal(x2, a2)
+
+
+def test_v3_pull_needs_local_parameters_and_a_valid_rho(oracle):
+    a, x, m, d = rng_state(12, 32, 2)
+    for bad in (0.0, -0.5, 1.5, float("nan")):
+        with pytest.raises(ValueError):
+            oracle.outer_step_variant_f32(seg_off=[0, 32], alpha=1.0, beta=0.9, phi=1.0, c=0.0, tau=2,
+                                          step=1, x=x, a=a, m=m, deltas=d, pull_rho=bad)
+    with pytest.raises(ValueError):
+        oracle.outer_step_variant_f32(seg_off=[0, 32], alpha=1.0, beta=0.9, phi=1.0, c=0.0, tau=2,
+                                      step=1, x=None, a=a, a_out=np.empty_like(a), m=m, deltas=d,
+                                      pull_rho=0.5)
+
+
+def test_v4_norm_rescale_against_the_library_and_its_bounds(oracle):
+    n, K, alpha, beta = 4000, 4, 0.7, 0.9
+    table = [0, 10, 10, 1200, 2600, n]
+    phi = 0.25
+    a, x, m, d = rng_state(13, n, K, m_std=0.02)
+    m[1200:2600] *= 0.01                                   # one segment well inside the threshold
+    a0, m0 = a.copy(), m.copy()
+    fs = f32([1e-3, 1e-3, 2e-3, 1e-3, 3e-3])
+    out = oracle.outer_step_variant_f32(seg_off=table, alpha=alpha, beta=beta, phi=phi, c=1.0, tau=2,
+                                        step=2, x=x, a=a, m=m, deltas=d, norm_clip=True,
+                                        first_step_norm=fs)
+    # same round without any clipping: the momentum is the same, rescaled segments differ in the iterate
+    a_u, x_u, m_u = a0.copy(), (a0 + 0).copy(), m0.copy()
+    # Lambda must be the norm-rescale one, so feed it through c*ratio by hand: re-run with norm_clip and phi=inf
+    free = oracle.outer_step_variant_f32(seg_off=table, alpha=alpha, beta=beta, phi=INF, c=0.0, tau=2,
+                                         step=2, x=x_u, a=a_u, m=m_u, deltas=d, norm_clip=True)
+    assert np.all(free["scale"] == 1.0) and free["nclipped"] == 0
+    rescaled = 0
+    for s in range(len(table) - 1):
+        lo, hi = table[s], table[s + 1]
+        if hi == lo:
+            assert out["scale"][s] == 1.0
+            continue
+        ms = m[lo:hi].astype(np.float64)
+        nrm = np.sqrt(np.dot(ms, ms))
+        step_norm = np.sqrt(np.sum((a[lo:hi].astype(np.float64) - a0[lo:hi]) ** 2))
+        assert step_norm <= alpha * phi * (1 + 1e-6)
+        # library: clip_grad_norm_ on a tensor whose .grad is this segment of m_t
+        g = torch.nn.Parameter(torch.zeros(hi - lo, dtype=torch.float64))
+        g.grad = torch.tensor(ms)
+        torch.nn.utils.clip_grad_norm_([g], max_norm=phi)
+        want = a0[lo:hi].astype(np.float64) - alpha * g.grad.numpy()
+        np.testing.assert_allclose(a[lo:hi], want, rtol=0, atol=1e-5 * alpha * phi)
+        if nrm > phi:
+            rescaled += hi - lo
+            np.testing.assert_allclose(out["scale"][s], phi / nrm, rtol=2e-7)
+            np.testing.assert_allclose(step_norm, alpha * phi, rtol=1e-6)
+            # direction kept: the step is a multiple of m_t
+            ratio = (a0[lo:hi].astype(np.float64) - a[lo:hi]) / ms
+            np.testing.assert_allclose(ratio, alpha * phi / nrm, rtol=5e-4)
+        else:
+            assert out["scale"][s] == 1.0
+            np.testing.assert_array_equal(a[lo:hi], f32(a0[lo:hi] - f32(alpha) * m[lo:hi]))
+    assert out["nclipped"] == rescaled and 0 < rescaled < n
+    np.testing.assert_array_equal(x, a)
+
+
+def test_v4_norm_rescale_numerator_is_the_measured_anchor_displacement(oracle):
+    """Eq. 3's numerator under norm rescale, alpha*min(||m_{t-1}||_s, phi), against
+    ||x_{t,0} - x_{t-1,0}||_s measured from saved anchors; Lambda - 1 = c*that/T."""
+    n, K, alpha, c, tau = 3000, 3, 0.8, 0.7, 3
+    table = [0, 700, 1900, n]
+    phi = 0.02
+    r = np.random.default_rng(14)
+    a = f32(r.normal(0, 0.02, n))
+    m = f32(r.normal(0, 4e-4, n))
+    m[700:1900] *= 10.0                                     # one segment far beyond the threshold
+    anchors = [a.copy()]
+    fs_hist = []
+    for t in range(1, 5):
+        x = f32(a + r.normal(0, 1e-3, n))
+        d = [f32(r.normal(0, 1e-3, n)) for _ in range(K)]
+        fs = f32(np.abs(r.normal(2e-3, 2e-4, 3)))
+        out = oracle.outer_step_variant_f32(seg_off=table, alpha=alpha, beta=0.9, phi=phi, c=c, tau=tau,
+                                            step=t, x=x, a=a, m=m, deltas=d, norm_clip=True,
+                                            first_step_norm=fs)
+        anchors.append(a.copy())
+        if t >= 2:
+            for s in range(3):
+                lo, hi = table[s], table[s + 1]
+                moved = np.sqrt(np.sum((anchors[t - 1][lo:hi].astype(np.float64) - anchors[t - 2][lo:hi]) ** 2))
+                want = c * moved / (tau * float(fs[s])) + 1.0
+                np.testing.assert_allclose(out["lam"][s], want, rtol=2e-6)
+            assert np.any(prev_scale < 1.0) and np.any(prev_scale == 1.0)
+        prev_scale = out["scale"]

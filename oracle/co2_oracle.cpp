@@ -485,6 +485,127 @@ int co2_oracle_outer_step_bf16(int64_t n, int32_t S, const int64_t* seg_off,
   return 0;
 }
 
+// IEEE binary16 transport of the pseudo-gradients: the same as the bf16 case with
+// the other 16-bit format (5 exponent bits, 10 fraction bits).
+//
+// fp32 -> binary16 bit pattern: round to nearest, ties to even; gradual underflow
+// to subnormals (multiples of 2^-24) and zero; magnitudes that round to 2^16 or
+// more become infinity; NaN stays a quiet NaN.
+uint16_t co2_oracle_f32_to_f16(float f) {
+  union { float f; uint32_t u; } cv;
+  cv.f = f;
+  const uint16_t sign = static_cast<uint16_t>((cv.u >> 16) & 0x8000u);
+  const uint32_t mag = cv.u & 0x7fffffffu;
+  if (mag > 0x7f800000u) return static_cast<uint16_t>(sign | 0x7e00u);      // NaN
+  if (mag >= 0x47800000u) return static_cast<uint16_t>(sign | 0x7c00u);      // >= 2^16, infinity
+  if (mag >= 0x38800000u) {                                                  // >= 2^-14: normal result
+    uint32_t r = mag - 0x38000000u;               // exponent bias 127 -> 15
+    const uint32_t lsb = (r >> 13) & 1u;          // last kept fraction bit decides ties
+    r += 0x0fffu + lsb;
+    return static_cast<uint16_t>(sign | (r >> 13));   // a carry out of the fraction reaches 0x7c00 = infinity
+  }
+  if (mag <= 0x33000000u) return sign;            // <= 2^-25: rounds to zero (2^-25 itself is a tie, even = 0)
+  // subnormal result: count of 2^-24 units, rounded to nearest even
+  const uint32_t e = mag >> 23;                   // 102 .. 112
+  const uint32_t sig = (mag & 0x007fffffu) | 0x00800000u;
+  const uint32_t shift = 126u - e;                // 14 .. 24
+  uint32_t h = sig >> shift;
+  const uint32_t rem = sig & ((1u << shift) - 1u);
+  const uint32_t half = 1u << (shift - 1u);
+  if (rem > half || (rem == half && (h & 1u))) ++h;
+  return static_cast<uint16_t>(sign | h);         // h == 0x400 is the smallest normal, as it should be
+}
+
+// binary16 bit pattern -> fp32, exact.
+float co2_oracle_f16_to_f32(uint16_t b) {
+  union { float f; uint32_t u; } cv;
+  const uint32_t sign = static_cast<uint32_t>(b & 0x8000u) << 16;
+  const uint32_t e = (b >> 10) & 0x1fu;
+  const uint32_t frac = b & 0x3ffu;
+  if (e == 0x1fu) {
+    cv.u = sign | 0x7f800000u | (frac << 13);
+  } else if (e != 0u) {
+    cv.u = sign | ((e + 112u) << 23) | (frac << 13);
+  } else {
+    cv.f = static_cast<float>(frac) * 5.9604644775390625e-08f;   // frac * 2^-24, exact
+    cv.u |= sign;
+  }
+  return cv.f;
+}
+
+// One outer update with binary16 pseudo-gradient buffers: co2_oracle_outer_step_bf16
+// with the conversions above.
+int co2_oracle_outer_step_f16(int64_t n, int32_t S, const int64_t* seg_off,
+                              int32_t K, float alpha, float beta, float phi,
+                              float c, int32_t tau, int64_t step,
+                              float* x, const float* a_in, float* a_out,
+                              float* m, const uint16_t* const* d, uint16_t* dout,
+                              const float* first_step_norm,
+                              float* lambda_out, int64_t* nclipped) {
+  if (check_table(n, S, seg_off) || !a_in || !a_out || !m) return -1;
+  if ((x == nullptr) != (dout == nullptr)) return -1;
+  if (K < 1 || tau < 1 || !(phi > 0.0f) || step < 0) return -1;
+  if (nclipped) *nclipped = 0;
+
+  if (step == 0) {
+    for (int64_t j = 0; j < n; ++j) {
+      float aj = a_in[j];
+      if (x) { dout[j] = co2_oracle_f32_to_f16(aj - x[j]); x[j] = aj; }
+      a_out[j] = aj;
+    }
+    if (lambda_out) for (int32_t s = 0; s < S; ++s) lambda_out[s] = 1.0f;
+    return 0;
+  }
+  if (!d) return -1;
+  for (int32_t k = 0; k < K; ++k) if (!d[k]) return -1;
+
+  const float rK = static_cast<float>(1.0 / static_cast<double>(K));
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t lo = seg_off[s], hi = seg_off[s + 1];
+    double M2 = 0.0;
+    for (int64_t j = lo; j < hi; ++j) {
+      double cm = static_cast<double>(clip_coord<float>(m[j], phi));
+      M2 += cm * cm;
+    }
+    double T;
+    if (first_step_norm) {
+      T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
+    } else {
+      double P2 = 0.0;
+      for (int64_t j = lo; j < hi; ++j) {
+        double dv = static_cast<double>(co2_oracle_f16_to_f32(d[0][j]));
+        P2 += dv * dv;
+      }
+      T = std::sqrt(P2);
+    }
+    double Lam = 1.0;
+    if (c != 0.0f && T != 0.0) {
+      Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * std::sqrt(M2) / T + 1.0;
+    }
+    const float inv = static_cast<float>(1.0 / Lam);
+    if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+
+    for (int64_t j = lo; j < hi; ++j) {
+      const float aj = a_in[j];
+      if (x) dout[j] = co2_oracle_f32_to_f16(aj - x[j]);
+      float sum = co2_oracle_f16_to_f32(d[0][j]);
+      for (int32_t k = 1; k < K; ++k) sum = sum + co2_oracle_f16_to_f32(d[k][j]);
+      const float dbar = sum * rK;
+      const float bm = beta * m[j];
+      const float pen = dbar * inv;
+      const float mt = bm + pen;
+      const float cm = clip_coord<float>(mt, phi);
+      const float stepv = alpha * cm;
+      const float xn = aj - stepv;
+      if (nclipped && (mt > phi || mt < -phi)) ++*nclipped;
+      m[j] = mt;
+      if (x) x[j] = xn;
+      a_out[j] = xn;
+    }
+  }
+  return 0;
+}
+
 // Local update with AdamW as the base optimizer (decoupled weight decay,
 // Loshchilov & Hutter): for inner step index k >= 1
 //   m1 <- b1*m1 + (1-b1)*g ;  v <- b2*v + (1-b2)*g*g

@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
 
 
 _ENTRY_POINTS = ("co2_oracle_sqnorms", "co2_oracle_outer_step_f32", "co2_oracle_outer_step_f64",
-                 "co2_oracle_outer_step_variant_f32",
+                 "co2_oracle_outer_step_variant_f32", "co2_oracle_outer_step_f16",
                  "co2_oracle_outer_step_bf16", "co2_oracle_adamw_f32", "co2_oracle_adamw_f64")
 
 
@@ -41,6 +41,10 @@ def _open(path):
     lib.co2_oracle_f32_to_bf16.argtypes = [C.c_float]
     lib.co2_oracle_bf16_to_f32.restype = C.c_float
     lib.co2_oracle_bf16_to_f32.argtypes = [C.c_uint16]
+    lib.co2_oracle_f32_to_f16.restype = C.c_uint16
+    lib.co2_oracle_f32_to_f16.argtypes = [C.c_float]
+    lib.co2_oracle_f16_to_f32.restype = C.c_float
+    lib.co2_oracle_f16_to_f32.argtypes = [C.c_uint16]
     return lib
 
 
@@ -213,8 +217,27 @@ def bf16_to_f32(bits):
     return np.array([lib.co2_oracle_bf16_to_f32(int(x)) for x in b], dtype=np.float32)
 
 
+def f32_to_f16(values):
+    """fp32 array -> IEEE binary16 bit patterns (uint16), element by element through the C loop."""
+    lib = _load()
+    v = np.asarray(values, dtype=np.float32).ravel()
+    return np.array([lib.co2_oracle_f32_to_f16(C.c_float(f)) for f in v], dtype=np.uint16)
+
+
+def f16_to_f32(bits):
+    lib = _load()
+    b = np.asarray(bits, dtype=np.uint16).ravel()
+    return np.array([lib.co2_oracle_f16_to_f32(int(x)) for x in b], dtype=np.float32)
+
+
+def outer_step_f16(**kw):
+    """Outer update with binary16 pseudo-gradient buffers (uint16 bit patterns).
+    Returns dict(dout (uint16), lam, nclipped)."""
+    return outer_step_bf16(_entry="co2_oracle_outer_step_f16", **kw)
+
+
 def outer_step_bf16(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
-                    a_out=None, first_step_norm=None):
+                    a_out=None, first_step_norm=None, _entry="co2_oracle_outer_step_bf16"):
     """Outer update with bf16 pseudo-gradient buffers (uint16 bit patterns).
     Returns dict(dout (uint16), lam, nclipped)."""
     lib = _load()
@@ -227,7 +250,7 @@ def outer_step_bf16(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
     ncl = C.c_int64(0)
     K = len(deltas) if deltas is not None else 1
     dptr = _ptr_array(deltas, np.uint16) if deltas is not None else None
-    rc = lib.co2_oracle_outer_step_bf16(
+    rc = getattr(lib, _entry)(
         C.c_int64(n), C.c_int32(S), _ptr(t, np.int64), C.c_int32(K),
         C.c_float(alpha), C.c_float(beta), C.c_float(phi), C.c_float(c),
         C.c_int32(tau), C.c_int64(step),
@@ -235,7 +258,7 @@ def outer_step_bf16(*, seg_off, alpha, beta, phi, c, tau, step, x, a, m, deltas,
         _ptr(m, np.float32), dptr, _ptr(dout, np.uint16),
         _ptr(first_step_norm, np.float32), _ptr(lam, np.float32), C.byref(ncl))
     if rc:
-        raise ValueError("co2_oracle_outer_step_bf16 rejected its arguments")
+        raise ValueError(f"{_entry} rejected its arguments")
     return dict(dout=dout, lam=lam, nclipped=ncl.value)
 
 

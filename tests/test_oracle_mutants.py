@@ -64,6 +64,18 @@ MUTANTS = [
     ("bf16_widening_shift_wrong", "cv.u = static_cast<uint32_t>(b) << 16;", "cv.u = static_cast<uint32_t>(b) << 15;"),
     ("bf16_step_skips_rounding_of_dout", "if (x) dout[j] = co2_oracle_f32_to_bf16(aj - x[j]);\n      float sum",
      "if (x) dout[j] = static_cast<uint16_t>(0);\n      float sum"),
+    ("f16_truncates_instead_of_rounding", "r += 0x0fffu + lsb;", "r += 0u;"),
+    ("f16_ties_round_away", "r += 0x0fffu + lsb;", "r += 0x1000u;"),
+    ("f16_exponent_rebias_wrong", "uint32_t r = mag - 0x38000000u;", "uint32_t r = mag - 0x38800000u;"),
+    ("f16_no_overflow_to_infinity", "if (mag >= 0x47800000u) return static_cast<uint16_t>(sign | 0x7c00u);",
+     "if (mag >= 0x47800000u) return static_cast<uint16_t>(sign | 0x7bffu);"),
+    ("f16_subnormals_flushed", "if (mag <= 0x33000000u) return sign;", "if (mag < 0x38800000u) return sign;"),
+    ("f16_subnormal_tie_rounds_up", "if (rem > half || (rem == half && (h & 1u))) ++h;", "if (rem >= half) ++h;"),
+    ("f16_widening_subnormal_scale", "* 5.9604644775390625e-08f;", "* 1.1920928955078125e-07f;"),
+    ("f16_widening_exponent", "cv.u = sign | ((e + 112u) << 23) | (frac << 13);", "cv.u = sign | ((e + 127u) << 23) | (frac << 13);"),
+    ("f16_step_reads_bf16_layout", "float sum = co2_oracle_f16_to_f32(d[0][j]);", "float sum = co2_oracle_bf16_to_f32(d[0][j]);"),
+    ("f16_step_skips_rounding_of_dout", "if (x) dout[j] = co2_oracle_f32_to_f16(aj - x[j]);\n      float sum",
+     "if (x) dout[j] = static_cast<uint16_t>(0);\n      float sum"),
     ("adamw_second_moment_not_squared", "const float v = beta2 * exp_avg_sq[j] + (omb2 * g) * g;",
      "const float v = beta2 * exp_avg_sq[j] + (omb2 * g);"),
     ("adamw_no_bias_correction_1", "const float step_size = static_cast<float>(static_cast<double>(lr) / bc1);",

@@ -461,6 +461,61 @@ def test_bf16_step_equals_f32_step_on_widened_inputs(oracle, fsn):
         np.testing.assert_array_equal(o2["dout"], to_bits(o1["dout"]))
 
 
+# ---------------------------------------------------------------- binary16 transport
+def test_f16_rounding_against_library_cast(oracle):
+    """The oracle's fp32->binary16 (nearest, ties to even, gradual underflow, overflow
+    to infinity) against numpy's cast: random values over the normal and subnormal
+    ranges, exact ties, the overflow boundary, zeros and infinities; and every one of
+    the 65536 bit patterns back to fp32."""
+    r = np.random.default_rng(22)
+    vals = (list(r.normal(0, 1e-3, 2000)) + list(r.normal(0, 1.0, 500)) + list(r.normal(0, 1e-6, 2000))
+            + list(r.normal(0, 3e-8, 500)) + list(r.normal(0, 3e4, 500)))
+    vals += [0.0, -0.0, 65504.0, 65519.996, 65520.0, 65536.0, -65520.0, 1e9, -1e9, np.inf, -np.inf,
+             2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * (1 + 2.0 ** -20), 3 * 2.0 ** -25, 2.0 ** -14,
+             2.0 ** -14 * (1 - 2.0 ** -11), 2.0 ** -14 * (1 - 2.0 ** -12), 1 + 2.0 ** -11,
+             1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -20, -(1 + 2.0 ** -11)]
+    v = np.array(vals, dtype=np.float32)
+    with np.errstate(over="ignore"):
+        want = v.astype(np.float16).view(np.uint16)
+    got = oracle.f32_to_f16(v)
+    np.testing.assert_array_equal(got, want)
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    back = oracle.f16_to_f32(every)
+    lib = every.view(np.float16).astype(np.float32)
+    both_nan = np.isnan(back) & np.isnan(lib)
+    np.testing.assert_array_equal(back[~both_nan], lib[~both_nan])
+    assert np.array_equal(np.isnan(back), np.isnan(lib))
+    nan = oracle.f32_to_f16(np.array([np.nan], np.float32))
+    assert np.isnan(oracle.f16_to_f32(nan)[0])
+
+
+@pytest.mark.parametrize("fsn", [False, True])
+def test_f16_step_equals_f32_step_on_widened_inputs(oracle, fsn):
+    """With binary16 buffers the update is the fp32 update applied to the widened
+    deltas (bit for bit), and delta_out is the fp32 delta rounded once."""
+    n, K = 3000, 5
+    seg = [0, 7, 7, 1500, n]
+    a, x, m, d = rng_state(23, n, K)
+    d[1][:50] *= 1e-4                                         # reach the subnormal range
+    to_bits = lambda v: np.asarray(v, np.float32).astype(np.float16).view(np.uint16)  # noqa: E731
+    widen = lambda b: b.view(np.float16).astype(np.float32)  # noqa: E731
+    d_bits = [to_bits(v) for v in d]
+    d_wide = [widen(b) for b in d_bits]
+    fs = f32([0.01, 0.02, 0.03, 0.04]) if fsn else None
+    kw = dict(seg_off=seg, alpha=0.9, beta=0.9, phi=5e-3, c=1.0, tau=3, first_step_norm=fs)
+    for step in (0, 1):
+        a1, x1, m1 = a.copy(), x.copy(), m.copy()
+        o1 = oracle.outer_step_f32(x=x1, a=a1, m=m1, deltas=d_wide if step else None, step=step, **kw)
+        a2, x2, m2 = a.copy(), x.copy(), m.copy()
+        o2 = oracle.outer_step_f16(x=x2, a=a2, m=m2, deltas=d_bits if step else None, step=step, **kw)
+        np.testing.assert_array_equal(a1, a2)
+        np.testing.assert_array_equal(x1, x2)
+        np.testing.assert_array_equal(m1, m2)
+        np.testing.assert_array_equal(o1["lam"], o2["lam"])
+        assert o1["nclipped"] == o2["nclipped"]
+        np.testing.assert_array_equal(o2["dout"], to_bits(o1["dout"]))
+
+
 # ---------------------------------------------------------------- variants of the outer rule
 # V0 hand-expanded example per switch (tests/golden)
 # V1 every switch off == outer_step_f32, bit for bit

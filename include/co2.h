@@ -17,10 +17,11 @@
  *
  * Conventions
  *   - Pointers marked DEVICE point to GPU memory owned by the caller; pointers
- *     marked HOST point to ordinary host memory.  Apart from the optional
- *     co2_buffer_set_* pair at the end, the library allocates nothing, keeps
- *     no state between calls (co2_outer_step_static alone works in a scratch
- *     array of the library's own), and never synchronises: every call
+ *     marked HOST point to ordinary host memory.  Nothing declared in this
+ *     header allocates (the optional memory-layout service that does is in
+ *     co2_layout.h), reads the environment or keeps state between calls
+ *     (co2_outer_step_static alone works in a scratch array of the library's
+ *     own), and nothing synchronises: every call
  *     validates its arguments on the host, enqueues kernels on `hip_stream`
  *     (a hipStream_t; NULL = the null stream) and returns.  The launches hold
  *     no memset and no host callback, so a caller may capture them into a HIP
@@ -64,8 +65,8 @@ enum {
   CO2_OK = 0,
   CO2_EINVAL = -1,      /* bad argument (NULL, range, alignment, aliasing)  */
   CO2_EWORKSPACE = -2,  /* workspace NULL or smaller than co2_workspace_bytes */
-  CO2_EHIP = -3,        /* a HIP call failed (launch, or allocation in
-                           co2_buffer_set_create); see co2_last_hip_error()  */
+  CO2_EHIP = -3,        /* a HIP call failed (a launch; an allocation in
+                           co2_layout.h's calls); see co2_last_hip_error()   */
   CO2_ESCRATCH = -4     /* co2_outer_step_static: the sizes need more scratch than
                            CO2_STATIC_SCRATCH_BYTES                          */
 };
@@ -80,6 +81,32 @@ enum {
  * and n, the segment table and clip_phi are the same.  Results are identical to
  * the two-pass form up to the summation order of the fp64 norms. */
 #define CO2_FLAG_CARRIED_NORMS 1u
+/* Variants of the outer rule (the family CO2 is built on or compared with).
+ * They combine freely with each other and with the penalty and the clipping;
+ * only the fp32 entry points (co2_outer_step, co2_outer_step_static) take them.
+ *
+ * CO2_FLAG_CURRENT_ROUND: the momentum line in the order of Section 3.2's
+ *   recursion m_{t+1} = beta m_t + (x_{t,0} - x_{t,tau}) before the staleness is
+ *   introduced: the mean is taken over THIS round's pseudo-gradients, the
+ *   worker's own anchor - params (formed in this call) first, then
+ *   deltas[1..K-1], which must hold the peers' pseudo-gradients of this round.
+ *   deltas[0] is not read (may be NULL).  Round 0 is an ordinary round.  With
+ *   penalty_c = 0 and clip_phi = +INF this is the slow-momentum update.  Needs
+ *   params; a penalty (penalty_c != 0) needs first_step_norm.
+ * CO2_FLAG_ANCHOR_PULL: the local parameters do not restart from the new outer
+ *   iterate but are pulled towards it, params = x - pull_rho*(x - x_{t+1,0})
+ *   (the anchor-model rule of the overlap variant of local SGD discussed in the
+ *   paper's Discussions section); anchor_out still receives x_{t+1,0}.  Needs
+ *   params; pull_rho in (0,1], 1 being the plain restart.
+ * CO2_FLAG_NORM_CLIP: clipping by rescaling instead of Section 3.3's coordinate-
+ *   wise clamp (not in the paper): per segment Clip_norm(m, phi) = m*min(1,
+ *   phi/||m||_s), and Eq. 3's numerator ||x_{t,0} - x_{t-1,0}||_s becomes
+ *   alpha*min(||m_{t-1}||_s, phi).  The outer iterate needs ||m_t||_s, so it is
+ *   written by a second, lighter kernel (36+4K instead of 28+4K bytes per
+ *   coordinate).  clipped_out is not available. */
+#define CO2_FLAG_CURRENT_ROUND 2u
+#define CO2_FLAG_ANCHOR_PULL 4u
+#define CO2_FLAG_NORM_CLIP 8u
 
 /* Hyper-parameters and shape of one outer update (Algorithm 1's inputs).
  * Passed by pointer, read on the host only. */
@@ -104,6 +131,11 @@ typedef struct co2_params {
   int64_t* clipped_out;       /* optional DEVICE int64[S]: per segment, the number of coordinates
                                  with |m_t| > phi, i.e. clamped in the outer iterate (0 at
                                  step 0).  Costs two small extra launches when set.       */
+  float pull_rho;             /* CO2_FLAG_ANCHOR_PULL: rho in (0,1]; ignored otherwise     */
+  int32_t sweep_waves_per_cu; /* tuning: resident wavefronts per compute unit the sweep kernel
+                                 is capped to; 0 = the library's measured default (4..8 by K).
+                                 Lower it (2..4) for a sweep that shares the GPU with another
+                                 bandwidth-bound kernel on a second stream.  Range 0..32.  */
 } co2_params;
 
 /* Bytes of DEVICE workspace the calls below need for these sizes (256-byte
@@ -148,10 +180,19 @@ size_t co2_workspace_bytes(int64_t n, int32_t S, int32_t K);
  * step == 0: delta_out = anchor - params; params = anchor_out = anchor; momentum
  * is only read (its clipped sum of squares is left in the workspace for round 1).
  *
- * Buffers must not overlap except anchor_out == anchor.  Errors: CO2_EINVAL for
- * NULL/misaligned/overlapping buffers, n<1, S<1, K outside 1..CO2_MAX_K, a bad
- * segment table, beta outside [0,1), phi<=0 or NaN, c<0, tau<1, step<0,
- * non-finite alpha, unknown flags; CO2_EWORKSPACE; CO2_EHIP. */
+ * With CO2_FLAG_* variants (see the flags): dbar leads with the worker's own
+ * anchor[j] - params[j] and continues over deltas[1..K-1] (CURRENT_ROUND);
+ * params[j] = x - pull_rho*(x - x') with x the incoming params[j] (ANCHOR_PULL);
+ * per segment scale = (||m'||_s > phi) ? (float)(phi/||m'||_s) : 1 in fp64 and
+ * x' = anchor[j] - alpha*(m'*scale), M2 = sum_j momentum_in[j]^2 and the
+ * numerator of Lambda is alpha*min(sqrt(M2), phi) (NORM_CLIP).
+ *
+ * Buffers must not overlap except anchor_out == anchor (no output, small or
+ * large, may overlap any other argument or the workspace).  Errors: CO2_EINVAL
+ * for NULL/misaligned/overlapping buffers, n<1, S<1, K outside 1..CO2_MAX_K, a
+ * bad segment table, beta outside [0,1), phi<=0 or NaN, c<0, tau<1, step<0,
+ * non-finite alpha, unknown or inconsistent flags, pull_rho outside (0,1],
+ * sweep_waves_per_cu outside 0..32; CO2_EWORKSPACE; CO2_EHIP. */
 int co2_outer_step(const co2_params* p,
                    float* params, const float* anchor, float* anchor_out,
                    float* momentum, const float* const* deltas, float* delta_out,
@@ -209,6 +250,17 @@ int co2_outer_step_bf16(const co2_params* p,
                         const float* first_step_norm, float* lambda_out,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* As co2_outer_step_bf16 with IEEE fp16 bit patterns (round to nearest even,
+ * gradual underflow, overflow to infinity): 11 bits of significand instead of
+ * 8, but pseudo-gradient coordinates below 6e-8 in magnitude vanish and those
+ * below 6.1e-5 lose precision gradually. */
+int co2_outer_step_f16(const co2_params* p,
+                       float* params, const float* anchor, float* anchor_out,
+                       float* momentum, const uint16_t* const* deltas_f16,
+                       uint16_t* delta_out_f16,
+                       const float* first_step_norm, float* lambda_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Segmented sums of squares (the quantities under the roots of Eq. 3's norms).
  * Uses p->n, p->S, p->seg_off, p->seg_off_dev and p->clip_phi only.
  *
@@ -219,7 +271,9 @@ int co2_outer_step_bf16(const co2_params* p,
  *               the momentum row is last.  Sums of squares, not roots, so that
  *               shards of one tensor can be added before the root is taken.
  * fp64 accumulation in a fixed order: results are deterministic, and equal to
- * an ascending-index fp64 sum up to fp64 rounding.  Errors as above. */
+ * an ascending-index fp64 sum up to fp64 rounding.  The call works in a part of
+ * the workspace of its own: sums that a previous co2_outer_step left there for
+ * CO2_FLAG_CARRIED_NORMS stay valid.  Errors as above. */
 int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t nbuf,
                           const float* momentum, double* sqnorm_out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -261,39 +315,6 @@ int co2_sqrt_to_f32(const double* sq, float* out, int32_t S, void* hip_stream);
  * yardstick for attainable HBM bandwidth and for calibrating byte counters.
  * Moves 8 bytes per element. */
 int co2_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream);
-
-/* ---------------------------------------------------------------------------
- * Buffers placed for the sweep (optional; every entry point above works on any
- * device memory).  Not part of the paper's method: a memory-layout service for
- * callers that own their allocation.
- *
- * co2_buffer_set_create allocates `count` device buffers of bytes[i] bytes
- * (HOST array) and stores their DEVICE addresses in bufs_out[i] (HOST array).
- * Each buffer is an ordinary flat, contiguous range of device addresses,
- * 4 KiB aligned, readable and writable by every kernel and copy on the current
- * device.  Physically, every buffer is cut into the same number P of pieces
- * (about piece_bytes each for the largest buffer; 0 = 1 GiB; must be a
- * multiple of 2 MiB) and the pieces are obtained from the driver in the order
- * piece 0 of every buffer, piece 1 of every buffer, ...: the parts of the
- * buffers that the sweep touches at the same time are then neighbours in
- * device memory, which makes the sweep's duration less dependent on what the
- * driver's allocator hands out than K + 4 separate gigabyte-sized allocations.
- * Buffers of different element size (fp32 vectors and bf16 pseudo-gradients)
- * get pieces in the same proportion, so piece j always covers the same element
- * range.  Memory use: sum of bytes[i] rounded up to P * 2 MiB per buffer.
- *
- * Ownership: the set owns the memory until co2_buffer_set_destroy, which the
- * caller invokes after all work on the buffers has completed (it does not
- * synchronise).  These two calls are the only ones in the library that
- * allocate or free; they use HIP's virtual-memory-management calls on the
- * current device and return CO2_EHIP (co2_last_hip_error() holds the
- * hipError_t, e.g. out of memory) after releasing whatever they had obtained.
- */
-#define CO2_MAX_BUFFER_SET 64
-typedef struct co2_buffer_set co2_buffer_set;
-int co2_buffer_set_create(int32_t count, const size_t* bytes, size_t piece_bytes, void** bufs_out,
-                          co2_buffer_set** set_out);
-int co2_buffer_set_destroy(co2_buffer_set* set);
 
 /* Text for an error code (static string, never NULL). */
 const char* co2_strerror(int code);

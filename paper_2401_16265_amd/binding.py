@@ -16,6 +16,9 @@ CO2_MAX_K = 16
 CO2_MAX_NORM_BUFS = 32
 CO2_FLAG_NONE = 0
 CO2_FLAG_CARRIED_NORMS = 1
+CO2_FLAG_CURRENT_ROUND = 2
+CO2_FLAG_ANCHOR_PULL = 4
+CO2_FLAG_NORM_CLIP = 8
 CO2_MAX_BUFFER_SET = 64
 
 
@@ -27,7 +30,7 @@ class Co2Params(C.Structure):
         ("alpha", C.c_float), ("beta", C.c_float), ("clip_phi", C.c_float),
         ("penalty_c", C.c_float), ("tau", C.c_int32), ("flags", C.c_uint32),
         ("step", C.c_int64), ("ev_sweep_begin", C.c_void_p), ("ev_sweep_end", C.c_void_p),
-        ("clipped_out", C.c_void_p),
+        ("clipped_out", C.c_void_p), ("pull_rho", C.c_float), ("sweep_waves_per_cu", C.c_int32),
     ]
 
 
@@ -64,6 +67,8 @@ def lib() -> C.CDLL:
         L.co2_outer_step_static.argtypes = [C.POINTER(Co2Params)] + [C.c_void_p] * 8 + [C.c_void_p]
         L.co2_outer_step_bf16.restype = C.c_int
         L.co2_outer_step_bf16.argtypes = L.co2_outer_step.argtypes
+        L.co2_outer_step_f16.restype = C.c_int
+        L.co2_outer_step_f16.argtypes = L.co2_outer_step.argtypes
         L.co2_pseudo_grad_norms.restype = C.c_int
         L.co2_pseudo_grad_norms.argtypes = [C.POINTER(Co2Params), C.c_void_p, C.c_int32, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -236,8 +241,10 @@ def _check(rc: int, where: str, check: bool) -> int:
 def make_params(table: SegmentTable, K: int, alpha: float, beta: float, clip_phi: float,
                 penalty_c: float, tau: int, step: int, flags: int = 0,
                 ev_begin: Optional[HipEvent] = None, ev_end: Optional[HipEvent] = None,
-                clipped_out: Optional[torch.Tensor] = None) -> Co2Params:
-    return Co2Params(n=table.n, S=table.S, K=K, seg_off=table.host_ptr, seg_off_dev=table.dev_ptr,
+                clipped_out: Optional[torch.Tensor] = None, pull_rho: float = 1.0,
+                sweep_waves_per_cu: int = 0) -> Co2Params:
+    return Co2Params(pull_rho=pull_rho, sweep_waves_per_cu=sweep_waves_per_cu,
+                     n=table.n, S=table.S, K=K, seg_off=table.host_ptr, seg_off_dev=table.dev_ptr,
                      alpha=alpha, beta=beta, clip_phi=clip_phi, penalty_c=penalty_c, tau=tau,
                      flags=flags, step=step,
                      ev_sweep_begin=ev_begin.handle if ev_begin else None,
@@ -253,7 +260,7 @@ def co2_outer_step(p: Co2Params, params, anchor, anchor_out, momentum, deltas, d
     if deltas is not None:
         if len(deltas) != p.K:
             raise ValueError(f"{len(deltas)} delta buffers for K={p.K}")
-        dptrs = (C.c_void_p * len(deltas))(*[_dp(d, f32) for d in deltas])
+        dptrs = (C.c_void_p * len(deltas))(*[_dp(d, f32) for d in deltas])   # an entry may be None
     rc = lib().co2_outer_step(
         C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),
         dptrs, _dp(delta_out, f32), _dp(first_step_norm, f32), _dp(lambda_out, f32),
@@ -303,6 +310,32 @@ def co2_outer_step_bf16(p: Co2Params, params, anchor, anchor_out, momentum, delt
         _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream))
     return _check(rc, "co2_outer_step_bf16", check)
+
+
+def _f16_ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if t.dtype not in (torch.float16, torch.uint16, torch.int16):
+        raise ValueError("expected a tensor of fp16 values / bit patterns")
+    return _dp(t)
+
+
+def co2_outer_step_f16(p: Co2Params, params, anchor, anchor_out, momentum, deltas_f16,
+                       delta_out_f16, first_step_norm, lambda_out, workspace, stream=None,
+                       check: bool = True) -> int:
+    """int co2_outer_step_f16(...) -- see include/co2.h.  Delta tensors are torch.float16."""
+    f32 = torch.float32
+    dptrs = None
+    if deltas_f16 is not None:
+        if len(deltas_f16) != p.K:
+            raise ValueError(f"{len(deltas_f16)} delta buffers for K={p.K}")
+        dptrs = (C.c_void_p * len(deltas_f16))(*[_f16_ptr(d) for d in deltas_f16])
+    rc = lib().co2_outer_step_f16(
+        C.byref(p), _dp(params, f32), _dp(anchor, f32), _dp(anchor_out, f32), _dp(momentum, f32),
+        dptrs, _f16_ptr(delta_out_f16), _dp(first_step_norm, f32), _dp(lambda_out, f32),
+        _dp(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    return _check(rc, "co2_outer_step_f16", check)
 
 
 def co2_pseudo_grad_norms(p: Co2Params, bufs, momentum, sqnorm_out, workspace, stream=None,

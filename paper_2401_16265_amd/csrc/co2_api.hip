@@ -5,8 +5,8 @@
 // calls, the only ones that allocate, are in co2_buffers.hip.)
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
+#include <limits>
 #include <mutex>
 
 #include "co2.h"
@@ -57,6 +57,7 @@ struct Workspace {
   double* sub[2];          // [S*split] sub-sums of each segment's slots
   double* seg_sq;          // [2][S] per-segment sums
   float* inv;              // [S] 1/Lambda
+  float* scale;            // [S] norm-rescale factor min(1, phi/||m_t||_s)
   int split;               // workgroups sharing one segment's slots
   size_t bytes;
 };
@@ -88,20 +89,41 @@ inline Workspace layout(void* base, int64_t n, int32_t S) {
   w.sub[1] = reinterpret_cast<double*>(take(sub));
   w.seg_sq = reinterpret_cast<double*>(take(sizeof(double) * 2 * static_cast<size_t>(S)));
   w.inv = reinterpret_cast<float*>(take(sizeof(float) * static_cast<size_t>(S)));
+  w.scale = reinterpret_cast<float*>(take(sizeof(float) * static_cast<size_t>(S)));
   w.bytes = o;
   return w;
 }
 
-// Stage 2 of the gap: slots -> per-segment sub-sums -> Lambda, 1/Lambda.
+// Longest segment of a table, in elements.
+inline int64_t longest_segment(const co2_params* p) {
+  int64_t longest = 0;
+  for (int32_t s = 0; s < p->S; ++s) {
+    const int64_t len = p->seg_off[s + 1] - p->seg_off[s];
+    if (len > longest) longest = len;
+  }
+  return longest;
+}
+
+// Segments that span at most this many slots have them added by one workgroup,
+// Lambda included: stage 2 is then one launch instead of two.
+constexpr int64_t kDirectSlots = 4096;
+
+// Stage 2 of the gap: slots -> (per-segment sub-sums ->) Lambda, 1/Lambda.
+// `use_d`: the denominator is the norm of the own previous pseudo-gradient
+// (column 1 of the slots); otherwise tau*first_step_norm, or none (Lambda = 1).
 inline hipError_t enqueue_lambda(const Workspace& w, int64_t tile_elems, const co2_params* p,
-                                 const float* first_step_norm, float* lambda_out,
-                                 hipStream_t st) {
-  const bool need_d0 = first_step_norm == nullptr;
-  hipError_t e = co2::launch_slot_sums(w.slots, 0, need_d0, p->seg_off_dev, p->S, tile_elems,
+                                 bool use_d, const float* first_step_norm, double numer_cap,
+                                 float* lambda_out, hipStream_t st) {
+  if (longest_segment(p) / tile_elems + 2 <= kDirectSlots)
+    return co2::launch_lambda_direct(w.slots, p->seg_off_dev, p->S, tile_elems, use_d, first_step_norm,
+                                     p->penalty_c, p->alpha, p->tau, numer_cap, w.seg_sq, w.inv,
+                                     lambda_out, st);
+  hipError_t e = co2::launch_slot_sums(w.slots, 0, use_d, p->seg_off_dev, p->S, tile_elems,
                                        w.split, w.sub[0], w.sub[1], st);
   if (e != hipSuccess) return e;
-  return co2::launch_lambda_finish(w.sub[0], w.sub[1], p->S, w.split, first_step_norm,
-                                   p->penalty_c, p->alpha, p->tau, w.seg_sq, w.inv, lambda_out, st);
+  return co2::launch_lambda_finish(w.sub[0], w.sub[1], use_d, p->S, w.split, first_step_norm,
+                                   p->penalty_c, p->alpha, p->tau, numer_cap, w.seg_sq, w.inv,
+                                   lambda_out, st);
 }
 
 inline hipError_t enqueue_totals(const Workspace& w, const co2::SlotRec* slots, int col,
@@ -143,46 +165,11 @@ int static_scratch_of_current_device(void** out) {
   return CO2_OK;
 }
 
-int env_int(const char* name, int fallback) {
-  const char* v = std::getenv(name);
-  if (!v || !*v) return fallback;
-  char* endp = nullptr;
-  const long x = std::strtol(v, &endp, 10);
-  if (endp == v || x < 0 || x > 64) return fallback;   // 0 = no cap
-  return static_cast<int>(x);
-}
-
 }  // namespace
 
 namespace co2 {
 
 void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
-
-const Tuning& tuning() {
-  // Re-read on every launch (a handful of getenv calls): tuning runs change the
-  // variables between calls within one process.
-  thread_local Tuning u;
-  // Measured optimum of resident wavefronts per compute unit for the sweep at
-  // 1.3B parameters, averaged over several buffer placements (each wavefront
-  // holds 1 KB x (3+K) streams of loads): 8 for K <= 4, 7 for K <= 9, 6 for
-  // K <= 12, 5 for K <= 14, 4 beyond.
-  const int sweep_override = env_int("CO2_SWEEP_WAVES", -1);
-  for (int k = 1; k <= CO2_MAX_K; ++k) {
-    const int w = k <= 4 ? 8 : k <= 9 ? 7 : k <= 12 ? 6 : k <= 14 ? 5 : 4;
-    u.sweep_waves_per_cu[k] = sweep_override >= 0 ? sweep_override : w;
-  }
-  // The other kernels follow the same rule of thumb (about 64 KB of loads in
-  // flight per compute unit): the norm pass holds 4 KB per buffer and
-  // wavefront, an AdamW wavefront 7 KB (9 KB with the anchor).
-  const int norm_override = env_int("CO2_NORM_WAVES", -1);
-  u.norm_waves_per_cu[0] = u.norm_waves_per_cu[2] = norm_override >= 0 ? norm_override : 8;
-  u.norm_waves_per_cu[1] = norm_override >= 0 ? norm_override : 16;
-  const int adam_override = env_int("CO2_ADAM_WAVES", -1);
-  u.adam_waves_per_cu[0] = adam_override >= 0 ? adam_override : 7;
-  u.adam_waves_per_cu[1] = adam_override >= 0 ? adam_override : 5;
-  u.copy_waves_per_cu = env_int("CO2_COPY_WAVES", 7);
-  return u;
-}
 
 unsigned throttle_lds_bytes(int waves_per_cu) {
   if (waves_per_cu <= 0) return 0;
@@ -219,12 +206,15 @@ int co2_last_hip_error(void) { return g_last_hip_error; }
 
 namespace {
 
-// Shared by co2_outer_step (fp32 pseudo-gradient buffers), co2_outer_step_bf16
-// (`bf16`: the K buffers and delta_out hold bf16 bit patterns) and
-// co2_outer_step_static (`use_static`: the workspace is the library's own
+constexpr uint32_t kVariantFlags = CO2_FLAG_CURRENT_ROUND | CO2_FLAG_ANCHOR_PULL | CO2_FLAG_NORM_CLIP;
+constexpr uint32_t kAllFlags = CO2_FLAG_CARRIED_NORMS | kVariantFlags;
+
+// Shared by co2_outer_step (fp32 pseudo-gradient buffers), co2_outer_step_bf16 /
+// co2_outer_step_f16 (`dtype`: the K buffers and delta_out hold 16-bit patterns)
+// and co2_outer_step_static (`use_static`: the workspace is the library's own
 // per-GPU scratch array; `workspace` and `workspace_bytes` are ignored).
 int outer_step_impl(const co2_params* p, float* params, const float* anchor, float* anchor_out,
-                    float* momentum, const void* const* deltas, void* delta_out, bool bf16,
+                    float* momentum, const void* const* deltas, void* delta_out, int dtype,
                     const float* first_step_norm, float* lambda_out, void* workspace,
                     size_t workspace_bytes, bool use_static, void* hip_stream) {
   // ---- validation (no side effects before it passes)
@@ -236,17 +226,31 @@ int outer_step_impl(const co2_params* p, float* params, const float* anchor, flo
   if (!(p->beta >= 0.0f && p->beta < 1.0f)) return CO2_EINVAL;
   if (!(p->clip_phi > 0.0f)) return CO2_EINVAL;                 // also rejects NaN
   if (!(p->penalty_c >= 0.0f) || !std::isfinite(p->penalty_c)) return CO2_EINVAL;
-  if (p->flags & ~CO2_FLAG_CARRIED_NORMS) return CO2_EINVAL;
+  if (p->flags & ~kAllFlags) return CO2_EINVAL;
+  if (p->sweep_waves_per_cu < 0 || p->sweep_waves_per_cu > 32) return CO2_EINVAL;
   if (!anchor || !anchor_out || !momentum) return CO2_EINVAL;
   if ((params == nullptr) != (delta_out == nullptr)) return CO2_EINVAL;
-  const bool first = p->step == 0;
+  const bool current = (p->flags & CO2_FLAG_CURRENT_ROUND) != 0;
+  const bool norm_clip = (p->flags & CO2_FLAG_NORM_CLIP) != 0;
+  const bool pull_flag = (p->flags & CO2_FLAG_ANCHOR_PULL) != 0;
+  if ((p->flags & kVariantFlags) && dtype != co2::kDeltaF32) return CO2_EINVAL;
+  if (pull_flag && !(p->pull_rho > 0.0f && p->pull_rho <= 1.0f)) return CO2_EINVAL;
+  if ((current || pull_flag) && !params) return CO2_EINVAL;     // both need the local parameters
+  if (current && p->penalty_c != 0.0f && !first_step_norm) return CO2_EINVAL;
+  if (norm_clip && p->clipped_out) return CO2_EINVAL;
+  const bool first = p->step == 0 && !current;                   // stale order: round 0 forms delta_out only
   const bool carried = (p->flags & CO2_FLAG_CARRIED_NORMS) != 0;
-  if (first && carried) return CO2_EINVAL;
+  if (p->step == 0 && carried) return CO2_EINVAL;
+  // The denominator of Eq. 3: first-step norms, else the own previous pseudo-gradient's
+  // norm (stale order only), else none.
+  const bool need_d0 = first_step_norm == nullptr && !current;
   // Carried sums of delta_out^2 exist only if the previous call formed delta_out.
-  if (carried && !first_step_norm && !params) return CO2_EINVAL;
+  if (carried && need_d0 && !params) return CO2_EINVAL;
   const size_t nb = sizeof(float) * static_cast<size_t>(p->n);
-  const size_t db = (bf16 ? sizeof(uint16_t) : sizeof(float)) * static_cast<size_t>(p->n);
+  const size_t db = (dtype == co2::kDeltaF32 ? sizeof(float) : sizeof(uint16_t)) * static_cast<size_t>(p->n);
   const size_t sb = sizeof(float) * static_cast<size_t>(p->S);
+  const size_t cb = sizeof(int64_t) * static_cast<size_t>(p->S);
+  const size_t tb = sizeof(int64_t) * (static_cast<size_t>(p->S) + 1);
   const void* vec[5] = {params, anchor, momentum, delta_out, anchor_out == anchor ? nullptr : anchor_out};
   const size_t vecb[5] = {nb, nb, nb, db, nb};
   for (int i = 0; i < 5; ++i) {
@@ -257,41 +261,66 @@ int outer_step_impl(const co2_params* p, float* params, const float* anchor, flo
   if (!aligned16(p->seg_off_dev) || !aligned16(first_step_norm) || !aligned16(lambda_out) ||
       !aligned16(p->clipped_out))
     return CO2_EINVAL;
-  if (overlaps(first_step_norm, sb, lambda_out, sb)) return CO2_EINVAL;
+  // The per-segment arrays: no output among them may touch anything else.
+  const void* small[4] = {lambda_out, p->clipped_out, first_step_norm, p->seg_off_dev};
+  const size_t smallb[4] = {sb, cb, sb, tb};
+  for (int i = 0; i < 4; ++i) {
+    for (int j = i + 1; j < 4; ++j)
+      if ((i < 2 || j < 2) && overlaps(small[i], smallb[i], small[j], smallb[j])) return CO2_EINVAL;
+    for (int v = 0; v < 5; ++v) {
+      // the anchor is only read unless the update is in place
+      const bool writes = i < 2 || v != 1 || anchor_out == anchor;
+      if (writes && overlaps(small[i], smallb[i], vec[v], vecb[v])) return CO2_EINVAL;
+    }
+  }
   co2::DeltaPtrs dptr{};
+  int nbuf = 0;                                                  // buffers the sweep reads
   if (!first) {
-    if (!deltas) return CO2_EINVAL;
-    for (int k = 0; k < p->K; ++k) {
+    if (!deltas && !(current && p->K == 1)) return CO2_EINVAL;
+    for (int k = current ? 1 : 0; k < p->K; ++k) {
       const void* dk = deltas[k];
       if (!dk || !aligned16(dk)) return CO2_EINVAL;
       // inputs may repeat among themselves, but no output may touch them
       if (overlaps(dk, db, params, nb) || overlaps(dk, db, momentum, nb) ||
-          overlaps(dk, db, delta_out, db) || overlaps(dk, db, anchor_out, nb))
+          overlaps(dk, db, delta_out, db) || overlaps(dk, db, anchor_out, nb) ||
+          overlaps(dk, db, lambda_out, sb) || overlaps(dk, db, p->clipped_out, cb))
         return CO2_EINVAL;
-      dptr.p[k] = dk;
+      dptr.p[nbuf++] = dk;
     }
   }
   Workspace w = layout(use_static ? nullptr : workspace, p->n, p->S);
-  if (use_static) {
+  if (!use_static) {
+    if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
+    for (int i = 0; i < 5; ++i)
+      if (overlaps(vec[i], vecb[i], workspace, w.bytes)) return CO2_EINVAL;
+    for (int i = 0; i < 4; ++i)
+      if (overlaps(small[i], smallb[i], workspace, w.bytes)) return CO2_EINVAL;
+    for (int k = 0; k < nbuf; ++k)
+      if (overlaps(dptr.p[k], db, workspace, w.bytes)) return CO2_EINVAL;
+  } else {
     // Last step before the launches, after every argument check: the address of
     // this GPU's scratch array (no allocation; a table lookup after the first call).
     void* ptr = nullptr;
     const int rc = static_scratch_of_current_device(&ptr);
     if (rc != CO2_OK) return rc;
     w = layout(ptr, p->n, p->S);
-  } else {
-    if (!workspace || !aligned256(workspace) || workspace_bytes < w.bytes) return CO2_EWORKSPACE;
-    for (int i = 0; i < 5; ++i)
-      if (overlaps(vec[i], vecb[i], workspace, w.bytes)) return CO2_EINVAL;
   }
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const float inf = std::numeric_limits<float>::infinity();
   co2::SweepArgs g{};
   g.x = params; g.a_in = anchor; g.a_out = anchor_out; g.m = momentum; g.d = dptr;
-  g.dout = delta_out; g.bf16 = bf16; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
-  g.alpha = p->alpha; g.beta = p->beta; g.phi = p->clip_phi;
+  g.dout = delta_out; g.dtype = dtype; g.inv = w.inv; g.off_dev = p->seg_off_dev; g.S = p->S; g.n = p->n;
+  g.alpha = p->alpha; g.beta = p->beta;
+  // Under norm rescale the sweep clamps nothing and its slot sums are those of m' itself.
+  g.phi = norm_clip ? inf : p->clip_phi;
   g.rK = static_cast<float>(1.0 / static_cast<double>(p->K));
   g.slots = w.slots;
+  g.waves_per_cu = p->sweep_waves_per_cu;
+  g.mode.own_current = current;
+  g.mode.pull = pull_flag && p->pull_rho != 1.0f;
+  g.mode.rho = p->pull_rho;
+  g.mode.defer_iterate = norm_clip;
   const bool has_x = params != nullptr;
   hipError_t e;
 
@@ -306,24 +335,34 @@ int outer_step_impl(const co2_params* p, float* params, const float* anchor, flo
   }
 
   // ---- the two sums of squares of Eq. 3, then Lambda per segment
-  const bool need_d0 = first_step_norm == nullptr;
+  const double numer_cap = norm_clip ? static_cast<double>(p->clip_phi)
+                                     : std::numeric_limits<double>::infinity();
   if (carried) {
-    e = enqueue_lambda(w, co2::kSweepTile, p, first_step_norm, lambda_out, st);
+    e = enqueue_lambda(w, co2::kSweepTile, p, need_d0, first_step_norm, numer_cap, lambda_out, st);
   } else {
-    e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, p->clip_phi,
-                                    need_d0 ? dptr.p[0] : nullptr, 0.0f, bf16, p->seg_off_dev,
+    e = co2::launch_sqnorm_partials(need_d0 ? 2 : 1, momentum, norm_clip ? 0.0f : p->clip_phi,
+                                    need_d0 ? dptr.p[0] : nullptr, 0.0f, dtype, p->seg_off_dev,
                                     p->S, p->n, w.slots, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = enqueue_lambda(w, co2::kNormTile, p, first_step_norm, lambda_out, st);
+    e = enqueue_lambda(w, co2::kNormTile, p, need_d0, first_step_norm, numer_cap, lambda_out, st);
   }
   if (e != hipSuccess) return fail_hip(e);
 
   // ---- the fused sweep
   if (p->ev_sweep_begin && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_begin), st)) != hipSuccess)
     return fail_hip(e);
-  if ((e = co2::launch_fused_sweep(p->K, has_x, g, st)) != hipSuccess) return fail_hip(e);
+  if ((e = co2::launch_fused_sweep(nbuf, has_x, g, st)) != hipSuccess) return fail_hip(e);
   if (p->ev_sweep_end && (e = hipEventRecord(static_cast<hipEvent_t>(p->ev_sweep_end), st)) != hipSuccess)
     return fail_hip(e);
+  if (norm_clip) {
+    // ||m_t||_s from the sums the sweep just left -> scale -> the deferred outer iterate
+    e = co2::launch_slot_sums(w.slots, 0, false, p->seg_off_dev, p->S, co2::kSweepTile, w.split,
+                              w.sub[0], w.sub[1], st);
+    if (e != hipSuccess) return fail_hip(e);
+    if ((e = co2::launch_scale_finish(w.sub[0], p->S, w.split, p->clip_phi, w.scale, st)) != hipSuccess)
+      return fail_hip(e);
+    if ((e = co2::launch_apply_iterate(has_x, g, w.scale, st)) != hipSuccess) return fail_hip(e);
+  }
   if (p->clipped_out && (e = enqueue_counts(w, p, st)) != hipSuccess) return fail_hip(e);
   return CO2_OK;
 }
@@ -337,7 +376,7 @@ int co2_outer_step(const co2_params* p, float* params, const float* anchor, floa
                    const float* first_step_norm, float* lambda_out, void* workspace,
                    size_t workspace_bytes, void* hip_stream) {
   return outer_step_impl(p, params, anchor, anchor_out, momentum,
-                         reinterpret_cast<const void* const*>(deltas), delta_out, false,
+                         reinterpret_cast<const void* const*>(deltas), delta_out, co2::kDeltaF32,
                          first_step_norm, lambda_out, workspace, workspace_bytes, false, hip_stream);
 }
 
@@ -346,7 +385,7 @@ int co2_outer_step_static(const co2_params* p, float* params, const float* ancho
                           float* delta_out, const float* first_step_norm, float* lambda_out,
                           void* hip_stream) {
   return outer_step_impl(p, params, anchor, anchor_out, momentum,
-                         reinterpret_cast<const void* const*>(deltas), delta_out, false,
+                         reinterpret_cast<const void* const*>(deltas), delta_out, co2::kDeltaF32,
                          first_step_norm, lambda_out, nullptr, 0, true, hip_stream);
 }
 
@@ -356,8 +395,20 @@ int co2_outer_step_bf16(const co2_params* p, float* params, const float* anchor,
                         float* lambda_out, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
   return outer_step_impl(p, params, anchor, anchor_out, momentum,
-                         reinterpret_cast<const void* const*>(deltas_bf16), delta_out_bf16, true,
-                         first_step_norm, lambda_out, workspace, workspace_bytes, false, hip_stream);
+                         reinterpret_cast<const void* const*>(deltas_bf16), delta_out_bf16,
+                         co2::kDeltaBF16, first_step_norm, lambda_out, workspace, workspace_bytes, false,
+                         hip_stream);
+}
+
+int co2_outer_step_f16(const co2_params* p, float* params, const float* anchor,
+                       float* anchor_out, float* momentum, const uint16_t* const* deltas_f16,
+                       uint16_t* delta_out_f16, const float* first_step_norm,
+                       float* lambda_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  return outer_step_impl(p, params, anchor, anchor_out, momentum,
+                         reinterpret_cast<const void* const*>(deltas_f16), delta_out_f16,
+                         co2::kDeltaF16, first_step_norm, lambda_out, workspace, workspace_bytes, false,
+                         hip_stream);
 }
 
 int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t nbuf,
@@ -383,6 +434,7 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
       return CO2_EINVAL;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  static_assert(co2::kAdamTile <= co2::kNormTile, "the AdamW slot region must hold the norm pass's slots");
   // Rows are reduced two at a time (two read streams per launch); launches on
   // one stream run in order, so the partial slots can be reused.
   for (int r = 0; r < rows; r += 2) {
@@ -391,14 +443,16 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
     const float phi0 = r < nbuf ? 0.0f : p->clip_phi;
     const float* b1 = pair ? (r + 1 < nbuf ? bufs[r + 1] : momentum) : nullptr;
     const float phi1 = pair ? (r + 1 < nbuf ? 0.0f : p->clip_phi) : 0.0f;
-    hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, false,
-                                               p->seg_off_dev, p->S, p->n, w.slots, st);
+    // partials go to the AdamW slot region (large enough: its tiles are smaller), so
+    // the sums an earlier sweep carried in w.slots for the next round stay intact
+    hipError_t e = co2::launch_sqnorm_partials(pair ? 2 : 1, b0, phi0, b1, phi1, co2::kDeltaF32,
+                                               p->seg_off_dev, p->S, p->n, w.adam_slots, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = enqueue_totals(w, w.slots, 0, co2::kNormTile, p->seg_off_dev, p->S,
+    e = enqueue_totals(w, w.adam_slots, 0, co2::kNormTile, p->seg_off_dev, p->S,
                        sqnorm_out + static_cast<size_t>(r) * p->S, st);
     if (e != hipSuccess) return fail_hip(e);
     if (pair) {
-      e = enqueue_totals(w, w.slots, 1, co2::kNormTile, p->seg_off_dev, p->S,
+      e = enqueue_totals(w, w.adam_slots, 1, co2::kNormTile, p->seg_off_dev, p->S,
                          sqnorm_out + static_cast<size_t>(r + 1) * p->S, st);
       if (e != hipSuccess) return fail_hip(e);
     }

@@ -1,5 +1,5 @@
 // co2_buffer_set: device buffers for the flat vectors of the update, placed for
-// the sweep (see include/co2.h).  Host code only: HIP virtual-memory-management
+// the sweep (see include/co2_layout.h).  Host code only: HIP virtual-memory-management
 // calls, no kernels.
 //
 // The sweep reads element e of every buffer at the same time.  With ordinary
@@ -16,7 +16,7 @@
 #include <new>
 #include <vector>
 
-#include "co2.h"
+#include "co2_layout.h"
 #include "co2_launch.hpp"
 
 struct co2_buffer_set {

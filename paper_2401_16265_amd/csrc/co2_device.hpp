@@ -39,8 +39,11 @@ struct alignas(32) SlotRec {
   double v[4];
 };
 
-// The K workers' pseudo-gradient buffers: fp32, or bf16 bit patterns for the
-// reduced-precision transport variant.
+// Storage type of the pseudo-gradient buffers (the payload of the all-reduce):
+// fp32, or bf16 / IEEE fp16 bit patterns for reduced-precision transport.
+enum DeltaType : int { kDeltaF32 = 0, kDeltaBF16 = 1, kDeltaF16 = 2 };
+
+// The workers' pseudo-gradient buffers that one sweep reads.
 struct DeltaPtrs {
   const void* p[CO2_MAX_K];
 };
@@ -170,14 +173,25 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
 }
 
+// fp32 <-> IEEE fp16 through the hardware conversions (round to nearest even,
+// gradual underflow, overflow to infinity).
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+  const _Float16 h = static_cast<_Float16>(f);
+  return static_cast<uint32_t>(__builtin_bit_cast(unsigned short, h));
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t bits16) {
+  const _Float16 h = __builtin_bit_cast(_Float16, static_cast<unsigned short>(bits16));
+  return static_cast<float>(h);
+}
+
 // How a pseudo-gradient buffer is read and written: four coordinates per lane
 // as one vector access, or one coordinate at a time on the element-wise path.
 // `stored(d)` is the value a reader of the buffer will see after `d` is written.
-template <bool BF16>
+template <int DT>
 struct DeltaIO;
 
 template <>
-struct DeltaIO<false> {
+struct DeltaIO<kDeltaF32> {
   using Vec = float4;
   // one row of 256 coordinates starting at element `row`
   static __device__ __forceinline__ Vec load4(const void* p, int64_t row, int lane) {
@@ -200,7 +214,7 @@ struct DeltaIO<false> {
 };
 
 template <>
-struct DeltaIO<true> {
+struct DeltaIO<kDeltaBF16> {
   using Vec = uint2;
   static __device__ __forceinline__ Vec load4(const void* p, int64_t row, int lane) {
     const v2u t = ld2_stream(static_cast<const uint16_t*>(p) + row, lane);
@@ -224,6 +238,34 @@ struct DeltaIO<true> {
   }
   static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
     static_cast<uint16_t*>(p)[j] = static_cast<uint16_t>(__float_as_uint(d) >> 16);
+  }
+};
+
+template <>
+struct DeltaIO<kDeltaF16> {
+  using Vec = uint2;
+  static __device__ __forceinline__ Vec load4(const void* p, int64_t row, int lane) {
+    const v2u t = ld2_stream(static_cast<const uint16_t*>(p) + row, lane);
+    return make_uint2(t.x, t.y);
+  }
+  static __device__ __forceinline__ float get(const Vec& v, int e) {
+    const uint32_t w = e < 2 ? v.x : v.y;
+    return f16_bits_to_f32((e & 1) ? (w >> 16) : (w & 0xffffu));
+  }
+  static __device__ __forceinline__ float load1(const void* p, int64_t j) {
+    return f16_bits_to_f32(static_cast<const uint16_t*>(p)[j]);
+  }
+  static __device__ __forceinline__ float stored(float d) {
+    return f16_bits_to_f32(f32_to_f16_bits(d));
+  }
+  // d[] already holds representable values (stored()), so the conversion is exact
+  static __device__ __forceinline__ void store4(void* p, int64_t base, int lane, const float (&d)[4]) {
+    const v2u t = {f32_to_f16_bits(d[0]) | (f32_to_f16_bits(d[1]) << 16),
+                   f32_to_f16_bits(d[2]) | (f32_to_f16_bits(d[3]) << 16)};
+    st2_stream(static_cast<uint16_t*>(p) + base, kWave * 8, lane, t);
+  }
+  static __device__ __forceinline__ void store1(void* p, int64_t j, float d) {
+    static_cast<uint16_t*>(p)[j] = static_cast<uint16_t>(f32_to_f16_bits(d));
   }
 };
 

@@ -8,14 +8,24 @@
 
 namespace co2 {
 
+// Run-time switches of the sweep (wavefront-uniform; see co2_sweep.hip).
+struct SweepMode {
+  bool own_current;         // the worker's own current pseudo-gradient leads the mean
+  bool pull;                // params = x - rho*(x - x') instead of x'
+  bool defer_iterate;       // norm-rescale clip: x' is written by apply_iterate afterwards
+  float rho;
+};
+
 struct SweepArgs {
   float* x;                 // params (nullable: split form)
   const float* a_in;        // anchor
   float* a_out;             // next anchor (may equal a_in)
   float* m;                 // momentum
-  DeltaPtrs d;              // K worker pseudo-gradients (fp32, or bf16 bits if bf16)
+  DeltaPtrs d;              // the pseudo-gradient buffers read (element type `dtype`)
   void* dout;               // delta_out (nullable with x), same element type as d
-  bool bf16;                // pseudo-gradient buffers hold bf16 bit patterns
+  int dtype;                // DeltaType of d and dout
+  SweepMode mode;
+  int waves_per_cu;         // resident-wavefront cap for the sweep; 0 = the library's default
   const float* inv;         // 1/Lambda per segment
   const int64_t* off_dev;   // segment table on the device
   int S;
@@ -40,26 +50,29 @@ struct AdamArgs {
   SlotRec* slots;           // per-slot sums of (p' - p_in)^2 in column 0, nullable
 };
 
-// Resident wavefronts per compute unit each streaming kernel is capped to
-// (0 = no cap).  Defaults come from bandwidth sweeps on MI355X; the environment
-// variables CO2_SWEEP_WAVES, CO2_NORM_WAVES, CO2_ADAM_WAVES and CO2_COPY_WAVES
-// override them (read at every launch) for tuning runs.
-struct Tuning {
-  int sweep_waves_per_cu[CO2_MAX_K + 1];
-  int norm_waves_per_cu[3];     // by number of buffers read (1 or 2)
-  int adam_waves_per_cu[2];     // [1]: the step that also reads the anchor and writes delta_out
-  int copy_waves_per_cu;
-};
-const Tuning& tuning();
+// Resident wavefronts per compute unit each streaming kernel is capped to.
+// Measured optima on MI355X at 1.3B parameters, averaged over several buffer
+// placements: about 56-64 KB of loads in flight per compute unit.  A sweep
+// wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront 4 KB
+// per buffer, an AdamW wavefront 7 KB (9 KB with the anchor).
+inline int default_sweep_waves(int delta_streams) {
+  return delta_streams <= 4 ? 8 : delta_streams <= 9 ? 7 : delta_streams <= 12 ? 6
+         : delta_streams <= 14 ? 5 : 4;
+}
+constexpr int kNormWavesOneBuffer = 16;
+constexpr int kNormWavesTwoBuffers = 8;
+constexpr int kAdamWavesPerCu = 7;
+constexpr int kAdamWavesWithAnchor = 5;   // the step that also reads the anchor and writes delta_out
+constexpr int kCopyWavesPerCu = 7;
 // Records `e` as this thread's most recent HIP error (what co2_last_hip_error() returns).
 void note_hip_error(hipError_t e);
 // Dynamic LDS bytes to request per single-wavefront workgroup so that at most
 // `waves_per_cu` of them fit on a compute unit.
 unsigned throttle_lds_bytes(int waves_per_cu);
 
-// b1 (optional second buffer) may hold bf16 bit patterns (b1_bf16).
+// b1 (optional second buffer) has element type b1_dtype (a DeltaType).
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const void* b1,
-                                  float phi1, bool b1_bf16, const int64_t* off_dev, int S,
+                                  float phi1, int b1_dtype, const int64_t* off_dev, int S,
                                   int64_t n, SlotRec* slots, hipStream_t st);
 // Sums column `col` (and col+1 if two) of each segment's slot records into
 // out_a (and out_b), `split` sub-sums per segment.
@@ -68,11 +81,23 @@ hipError_t launch_slot_sums(const SlotRec* slots, int col, bool two, const int64
                             hipStream_t st);
 hipError_t launch_totals_finish(const double* sub, int S, int split, double* out, hipStream_t st);
 hipError_t launch_counts_finish(const double* sub, int S, int split, int64_t* out, hipStream_t st);
-hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S, int split,
+// `use_d`: the denominator is sqrt of the sums in sub_d (else tau*first_step_norm, or
+// none at all: Lambda = 1).  `numer_cap`: upper bound of the numerator's norm (+inf: none).
+hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, bool use_d, int S, int split,
                                 const float* first_step_norm, float c, float alpha, int tau,
-                                double* seg_sq, float* inv, float* lambda_out, hipStream_t st);
+                                double numer_cap, double* seg_sq, float* inv, float* lambda_out,
+                                hipStream_t st);
+// Stage 2 in ONE launch for tables whose segments are short: each workgroup adds
+// its segment's slots and evaluates Lambda itself.
+hipError_t launch_lambda_direct(const SlotRec* slots, const int64_t* off_dev, int S, int64_t tile_elems,
+                                bool use_d, const float* first_step_norm, float c, float alpha, int tau,
+                                double numer_cap, double* seg_sq, float* inv, float* lambda_out,
+                                hipStream_t st);
+// scale[s] = min(1, phi/sqrt(sum)) from the per-segment sub-sums of m'^2.
+hipError_t launch_scale_finish(const double* sub, int S, int split, float phi, float* scale, hipStream_t st);
 hipError_t launch_sqrt_to_f32(const double* sq_in, float* out, int S, hipStream_t st);
-hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t st);   // g.bf16 selects the variant
+hipError_t launch_fused_sweep(int nbuf, bool has_x, const SweepArgs& g, hipStream_t st);  // nbuf buffers in g.d
+hipError_t launch_apply_iterate(bool has_x, const SweepArgs& g, const float* scale, hipStream_t st);
 hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st);
 hipError_t launch_adamw(const AdamArgs& g, hipStream_t st);

@@ -28,12 +28,12 @@ __device__ __forceinline__ void acc4(double& acc, float4 q, float phi) {
   acc += sq(q.x); acc += sq(q.y); acc += sq(q.z); acc += sq(q.w);
 }
 
-// NB buffers (1 or 2); the second may hold bf16 bit patterns (B1_BF16).
-template <int NB, bool B1_BF16>
+// NB buffers (1 or 2); the second has element type B1_DT (a DeltaType).
+template <int NB, int B1_DT>
 __global__ __launch_bounds__(kWave) void sqnorm_partials(
     const float* __restrict__ b0, float phi0, const void* __restrict__ b1, float phi1,
     const int64_t* __restrict__ off, int S, int64_t n, SlotRec* __restrict__ slots) {
-  using IO1 = DeltaIO<B1_BF16>;
+  using IO1 = DeltaIO<B1_DT>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kNormTile;
   const int lane = threadIdx.x;
@@ -147,32 +147,81 @@ __global__ __launch_bounds__(kReduceBlock) void counts_finish(
 }
 
 // Lambda_t per segment (Algorithm 1, gap update; Eq. 3), fp64:
-//   numerator   alpha*sqrt(M2),  M2 = sum Clip(m_{t-1},phi)^2
-//   denominator tau*first_step_norm[s], or sqrt(P2), P2 = sum d_0^2
-//   Lambda = (c == 0 || T == 0) ? 1 : (c*alpha)*sqrt(M2)/T + 1;  inv = (float)(1/Lambda)
-__global__ __launch_bounds__(kReduceBlock) void lambda_finish(
-    const double* __restrict__ sub_m, const double* __restrict__ sub_d, int S, int split,
-    const float* __restrict__ first_step_norm, float c, float alpha, int tau,
-    double* __restrict__ seg_sq, float* __restrict__ inv, float* __restrict__ lambda_out) {
-  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
-  if (s >= S) return;
-  const double M2 = add_in_order(sub_m, int64_t(s) * split, split);
-  double P2 = 0.0, T;
+//   numerator   alpha*min(sqrt(M2), cap),  M2 = sum Clip(m_{t-1},phi)^2  (cap = +inf unless
+//               clipping rescales by norm: then the previous step's norm is at most phi)
+//   denominator tau*first_step_norm[s], or sqrt(P2) with P2 = sum d_0^2, or none (Lambda = 1)
+//   Lambda = (c == 0 || T == 0) ? 1 : (c*alpha)*numerator_norm/T + 1;  inv = (float)(1/Lambda)
+__device__ __forceinline__ void lambda_of(double M2, double P2_sum, bool use_d,
+                                          const float* __restrict__ first_step_norm, int s, float c,
+                                          float alpha, int tau, double numer_cap, int S,
+                                          double* __restrict__ seg_sq, float* __restrict__ inv,
+                                          float* __restrict__ lambda_out) {
+  double P2 = 0.0, T = 0.0;
   if (first_step_norm) {
     T = static_cast<double>(tau) * static_cast<double>(first_step_norm[s]);
     P2 = T * T;
-  } else {
-    P2 = add_in_order(sub_d, int64_t(s) * split, split);
+  } else if (use_d) {
+    P2 = P2_sum;
     T = sqrt(P2);
   }
+  double moved = sqrt(M2);
+  if (moved > numer_cap) moved = numer_cap;
   double Lam = 1.0;
   if (c != 0.0f && T != 0.0) {
-    Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * sqrt(M2) / T + 1.0;
+    Lam = (static_cast<double>(c) * static_cast<double>(alpha)) * moved / T + 1.0;
   }
   seg_sq[s] = M2;
   seg_sq[S + s] = P2;
   inv[s] = static_cast<float>(1.0 / Lam);
   if (lambda_out) lambda_out[s] = static_cast<float>(Lam);
+}
+
+__global__ __launch_bounds__(kReduceBlock) void lambda_finish(
+    const double* __restrict__ sub_m, const double* __restrict__ sub_d, bool use_d, int S, int split,
+    const float* __restrict__ first_step_norm, float c, float alpha, int tau, double numer_cap,
+    double* __restrict__ seg_sq, float* __restrict__ inv, float* __restrict__ lambda_out) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
+  if (s >= S) return;
+  const double M2 = add_in_order(sub_m, int64_t(s) * split, split);
+  const double P2 = use_d ? add_in_order(sub_d, int64_t(s) * split, split) : 0.0;
+  lambda_of(M2, P2, use_d, first_step_norm, s, c, alpha, tau, numer_cap, S, seg_sq, inv, lambda_out);
+}
+
+// Stage 2 in one launch, for tables whose segments span few slots: workgroup s
+// adds the slots of segment s (fixed order) and evaluates Lambda itself.
+__global__ __launch_bounds__(kReduceBlock) void lambda_direct(
+    const SlotRec* __restrict__ slots, const int64_t* __restrict__ off, int S, int64_t tile_elems,
+    bool use_d, const float* __restrict__ first_step_norm, float c, float alpha, int tau,
+    double numer_cap, double* __restrict__ seg_sq, float* __restrict__ inv,
+    float* __restrict__ lambda_out) {
+  __shared__ double lds[2][kReduceWaves];
+  for (int s = blockIdx.x; s < S; s += gridDim.x) {
+    const int64_t lo = off[s], hi = off[s + 1];
+    double a = 0.0, b = 0.0;
+    if (hi > lo) {
+      const int64_t t0 = lo / tile_elems, t1 = (hi - 1) / tile_elems;
+      for (int64_t t = t0 + threadIdx.x; t <= t1; t += kReduceBlock) {
+        a += slots[t + s].v[0];
+        if (use_d) b += slots[t + s].v[1];
+      }
+    }
+    const double M2 = block_sum(a, lds[0]);
+    double P2 = 0.0;
+    if (use_d) P2 = block_sum(b, lds[1]);
+    if (threadIdx.x == 0)
+      lambda_of(M2, P2, use_d, first_step_norm, s, c, alpha, tau, numer_cap, S, seg_sq, inv, lambda_out);
+  }
+}
+
+// Norm-rescale clipping: scale[s] = min(1, phi/||m_t||_s) from the sub-sums of m_t^2.
+__global__ __launch_bounds__(kReduceBlock) void scale_finish(
+    const double* __restrict__ sub, int S, int split, float phi, float* __restrict__ scale) {
+  const int s = blockIdx.x * kReduceBlock + threadIdx.x;
+  if (s >= S) return;
+  const double nrm = sqrt(add_in_order(sub, int64_t(s) * split, split));
+  float f = 1.0f;
+  if (nrm > static_cast<double>(phi)) f = static_cast<float>(static_cast<double>(phi) / nrm);
+  scale[s] = f;
 }
 
 __global__ __launch_bounds__(kReduceBlock) void sqrt_to_f32(const double* __restrict__ sq_in,
@@ -184,18 +233,21 @@ __global__ __launch_bounds__(kReduceBlock) void sqrt_to_f32(const double* __rest
 // ---------------------------------------------------------------- launches
 
 hipError_t launch_sqnorm_partials(int nb, const float* b0, float phi0, const void* b1,
-                                  float phi1, bool b1_bf16, const int64_t* off_dev, int S,
+                                  float phi1, int b1_dtype, const int64_t* off_dev, int S,
                                   int64_t n, SlotRec* slots, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>((n + kNormTile - 1) / kNormTile)), block(kWave);
-  const unsigned lds = throttle_lds_bytes(tuning().norm_waves_per_cu[nb == 2 ? 2 : 1]);
-  if (nb == 2 && b1_bf16) {
-    hipLaunchKernelGGL((sqnorm_partials<2, true>), grid, block, lds, st, b0, phi0, b1, phi1,
+  const unsigned lds = throttle_lds_bytes(nb == 2 ? kNormWavesTwoBuffers : kNormWavesOneBuffer);
+  if (nb == 2 && b1_dtype == kDeltaBF16) {
+    hipLaunchKernelGGL((sqnorm_partials<2, kDeltaBF16>), grid, block, lds, st, b0, phi0, b1, phi1,
+                       off_dev, S, n, slots);
+  } else if (nb == 2 && b1_dtype == kDeltaF16) {
+    hipLaunchKernelGGL((sqnorm_partials<2, kDeltaF16>), grid, block, lds, st, b0, phi0, b1, phi1,
                        off_dev, S, n, slots);
   } else if (nb == 2) {
-    hipLaunchKernelGGL((sqnorm_partials<2, false>), grid, block, lds, st, b0, phi0, b1, phi1,
+    hipLaunchKernelGGL((sqnorm_partials<2, kDeltaF32>), grid, block, lds, st, b0, phi0, b1, phi1,
                        off_dev, S, n, slots);
   } else {
-    hipLaunchKernelGGL((sqnorm_partials<1, false>), grid, block, lds, st, b0, phi0,
+    hipLaunchKernelGGL((sqnorm_partials<1, kDeltaF32>), grid, block, lds, st, b0, phi0,
                        static_cast<const void*>(b0), 0.0f, off_dev, S, n, slots);
   }
   return hipGetLastError();
@@ -224,12 +276,30 @@ hipError_t launch_counts_finish(const double* sub, int S, int split, int64_t* ou
   return hipGetLastError();
 }
 
-hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, int S, int split,
+hipError_t launch_lambda_finish(const double* sub_m, const double* sub_d, bool use_d, int S, int split,
                                 const float* first_step_norm, float c, float alpha, int tau,
-                                double* seg_sq, float* inv, float* lambda_out, hipStream_t st) {
+                                double numer_cap, double* seg_sq, float* inv, float* lambda_out,
+                                hipStream_t st) {
   hipLaunchKernelGGL(lambda_finish, dim3((S + kReduceBlock - 1) / kReduceBlock),
-                     dim3(kReduceBlock), 0, st, sub_m, sub_d, S, split, first_step_norm, c, alpha,
-                     tau, seg_sq, inv, lambda_out);
+                     dim3(kReduceBlock), 0, st, sub_m, sub_d, use_d, S, split, first_step_norm, c,
+                     alpha, tau, numer_cap, seg_sq, inv, lambda_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_lambda_direct(const SlotRec* slots, const int64_t* off_dev, int S, int64_t tile_elems,
+                                bool use_d, const float* first_step_norm, float c, float alpha, int tau,
+                                double numer_cap, double* seg_sq, float* inv, float* lambda_out,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(lambda_direct, dim3(static_cast<unsigned>(S < 32768 ? S : 32768)),
+                     dim3(kReduceBlock), 0, st, slots, off_dev, S, tile_elems, use_d, first_step_norm,
+                     c, alpha, tau, numer_cap, seg_sq, inv, lambda_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_finish(const double* sub, int S, int split, float phi, float* scale,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(scale_finish, dim3((S + kReduceBlock - 1) / kReduceBlock), dim3(kReduceBlock), 0,
+                     st, sub, S, split, phi, scale);
   return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // The fused elementwise sweep of one CO2 outer update (CO2 paper, Algorithm 1:
 // momentum and outer-iterate lines; Section 3.3 for Clip), the first-round
-// kernel, and a plain copy kernel used as the bandwidth yardstick.
+// kernel, the deferred outer-iterate kernel of the norm-rescale variant, and a
+// plain copy kernel used as the bandwidth yardstick.
 //
 // Per coordinate j of segment s (fp32, every operation rounded once):
 //   delta_out[j] = anchor[j] - params[j]                       (this round's pseudo-gradient)
@@ -19,6 +20,17 @@
 // of Clip(m',phi)^2 and delta_out^2 per (tile, segment) slot: they are the two
 // sums of squares the NEXT round's gap needs, so a steady-state caller can skip
 // the separate norm pass.
+//
+// Variants of the rule (wavefront-uniform run-time switches, SweepMode):
+//   own_current    the mean runs over THIS round's pseudo-gradients (Section 3.2's
+//                  recursion before the staleness): the worker's own anchor - params
+//                  formed here comes first in the sum, followed by the buffers read;
+//   pull           the local parameters are pulled towards the new outer iterate,
+//                  params = x - rho*(x - x'), instead of restarting from it (the
+//                  anchor-model rule of the overlap variant of local SGD);
+//   defer_iterate  clipping by norm rescale: x' needs ||m'||_s, so this kernel only
+//                  writes m' and delta_out (and the slot sums, taken without the
+//                  coordinate clamp), and apply_iterate writes x' afterwards.
 #include "co2_device.hpp"
 #include "co2_launch.hpp"
 
@@ -28,11 +40,19 @@ struct SweepScalars {
   float alpha, beta, phi, rK;
 };
 
-template <int K>
-__device__ __forceinline__ float mean_of_workers(const float (&d)[K], float rK) {
-  float sum = d[0];
+// Sum over the workers, left to right, times 1/K.  With `own_first` the
+// worker's own current pseudo-gradient `own` is the first term and the NB
+// buffers follow; otherwise the NB buffers are all the terms (NB >= 1).
+template <int NB>
+__device__ __forceinline__ float mean_of_workers(const float* d, float own, bool own_first, float rK) {
+  float sum;
+  if constexpr (NB == 0) {
+    sum = own;
+  } else {
+    sum = own_first ? own + d[0] : d[0];
 #pragma unroll
-  for (int k = 1; k < K; ++k) sum = sum + d[k];
+    for (int k = 1; k < NB; ++k) sum = sum + d[k];
+  }
   return sum * rK;
 }
 
@@ -46,66 +66,76 @@ __device__ __forceinline__ float outer_coord(float a, float& m, float dbar, floa
   return a - stepv;
 }
 
+// What the local parameters become: the new outer iterate, or a step of rho
+// from the old local value towards it.
+__device__ __forceinline__ float local_after(float x_old, float x_new, bool pull, float rho) {
+  if (!pull) return x_new;
+  const float gap = x_old - x_new;
+  const float step = rho * gap;
+  return x_old - step;
+}
+
 __device__ __forceinline__ float comp(const float4& q, int e) {
   return e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
 }
 
-template <int K, bool HAS_X, bool BF16>
+template <int NB, bool HAS_X, int DT>
 struct SubTile {
   float4 va, vm, vx;
-  typename DeltaIO<BF16>::Vec vd[K];
+  typename DeltaIO<DT>::Vec vd[NB > 0 ? NB : 1];
 };
 
-template <int K, bool HAS_X, bool BF16>
-__device__ __forceinline__ void load_sub(SubTile<K, HAS_X, BF16>& t, const float* x,
+template <int NB, bool HAS_X, int DT>
+__device__ __forceinline__ void load_sub(SubTile<NB, HAS_X, DT>& t, const float* x,
                                          const float* a_in, const float* m, const DeltaPtrs& d,
                                          int64_t base, int lane) {
   t.va = ld4_stream(a_in + base, lane);
   t.vm = ld4_stream(m + base, lane);
   if (HAS_X) t.vx = ld4_stream(x + base, lane);
 #pragma unroll
-  for (int k = 0; k < K; ++k) t.vd[k] = DeltaIO<BF16>::load4(d.p[k], base, lane);
+  for (int k = 0; k < NB; ++k) t.vd[k] = DeltaIO<DT>::load4(d.p[k], base, lane);
 }
 
 // Update and store one 256-coordinate tile held in registers.
-template <int K, bool HAS_X, bool BF16>
-__device__ __forceinline__ void finish_sub(const SubTile<K, HAS_X, BF16>& t, float* x,
+template <int NB, bool HAS_X, int DT>
+__device__ __forceinline__ void finish_sub(const SubTile<NB, HAS_X, DT>& t, float* x,
                                            float* a_out, float* m, void* dout, int64_t base,
                                            int lane, float inv, const SweepScalars& h,
+                                           const SweepMode& mode,
                                            double& acc_m, double& acc_d, int& nclip) {
-  using IO = DeltaIO<BF16>;
-  float mc[4], xc[4], dc[4];
+  using IO = DeltaIO<DT>;
+  float mc[4], xc[4], dc[4], lc[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float ae = comp(t.va, e);
-    float dk[K];
+    float dk[NB > 0 ? NB : 1];
 #pragma unroll
-    for (int k = 0; k < K; ++k) dk[k] = IO::get(t.vd[k], e);
+    for (int k = 0; k < NB; ++k) dk[k] = IO::get(t.vd[k], e);
+    dc[e] = 0.0f;
     if (HAS_X) {
       dc[e] = IO::stored(ae - comp(t.vx, e));
       acc_d += sq(dc[e]);
     }
     mc[e] = comp(t.vm, e);
-    xc[e] = outer_coord(ae, mc[e], mean_of_workers<K>(dk, h.rK), inv, h);
+    xc[e] = outer_coord(ae, mc[e], mean_of_workers<NB>(dk, dc[e], mode.own_current, h.rK), inv, h);
+    if (HAS_X) lc[e] = local_after(comp(t.vx, e), xc[e], mode.pull, mode.rho);
     acc_m += sq(clip_coord(mc[e], h.phi));
     nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));   // wavefront-uniform count
   }
   constexpr int kTileBytes = kWave * 16;
-  const float4 xo = make_float4(xc[0], xc[1], xc[2], xc[3]);
-  if (HAS_X) {
-    IO::store4(dout, base, lane, dc);
-    st4_stream(x + base, kTileBytes, lane, xo);
-  }
+  if (HAS_X) IO::store4(dout, base, lane, dc);
   st4_stream(m + base, kTileBytes, lane, make_float4(mc[0], mc[1], mc[2], mc[3]));
-  st4_stream(a_out + base, kTileBytes, lane, xo);
+  if (mode.defer_iterate) return;
+  if (HAS_X) st4_stream(x + base, kTileBytes, lane, make_float4(lc[0], lc[1], lc[2], lc[3]));
+  st4_stream(a_out + base, kTileBytes, lane, make_float4(xc[0], xc[1], xc[2], xc[3]));
 }
 
-template <int K, bool HAS_X, bool BF16>
+template <int NB, bool HAS_X, int DT>
 __global__ __launch_bounds__(kWave) void fused_sweep(
     float* x, const float* a_in, float* a_out, float* m, DeltaPtrs d, void* dout,
     const float* __restrict__ inv_tab, const int64_t* __restrict__ off, int S, int64_t n,
-    SweepScalars h, SlotRec* __restrict__ slots) {
-  using IO = DeltaIO<BF16>;
+    SweepScalars h, SweepMode mode, SlotRec* __restrict__ slots) {
+  using IO = DeltaIO<DT>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int lane = threadIdx.x;
@@ -113,15 +143,15 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
 
   // The tile's loads go out before the segment lookup, which does not depend
   // on them and runs while they are in flight.
-  SubTile<K, HAS_X, BF16> cur;
-  if (full) load_sub<K, HAS_X, BF16>(cur, x, a_in, m, d, base, lane);
+  SubTile<NB, HAS_X, DT> cur;
+  if (full) load_sub<NB, HAS_X, DT>(cur, x, a_in, m, d, base, lane);
   const int s_lo = seg_of(off, S, base);
 
   if (full && base + kSweepTile <= off[s_lo + 1]) {
     const float inv = inv_tab[s_lo];
     double acc_m = 0.0, acc_d = 0.0;
     int nclip = 0;
-    finish_sub<K, HAS_X, BF16>(cur, x, a_out, m, dout, base, lane, inv, h, acc_m, acc_d, nclip);
+    finish_sub<NB, HAS_X, DT>(cur, x, a_out, m, dout, base, lane, inv, h, mode, acc_m, acc_d, nclip);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
@@ -141,21 +171,24 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     for (int64_t j = lo + lane; j < hi; j += kWave) {
       const float a = a_in[j];
       float mj = m[j];
-      float dk[K];
+      float dk[NB > 0 ? NB : 1];
 #pragma unroll
-      for (int k = 0; k < K; ++k) dk[k] = IO::load1(d.p[k], j);
-      float dj = 0.0f;
-      if (HAS_X) dj = IO::stored(a - x[j]);
-      const float xn = outer_coord(a, mj, mean_of_workers<K>(dk, h.rK), inv, h);
+      for (int k = 0; k < NB; ++k) dk[k] = IO::load1(d.p[k], j);
+      float dj = 0.0f, xj = 0.0f;
+      if (HAS_X) {
+        xj = x[j];
+        dj = IO::stored(a - xj);
+      }
+      const float xn = outer_coord(a, mj, mean_of_workers<NB>(dk, dj, mode.own_current, h.rK), inv, h);
       acc_m += sq(clip_coord(mj, h.phi));
       if (fabsf(mj) > h.phi) acc_c += 1.0;
       if (HAS_X) {
         acc_d += sq(dj);
         IO::store1(dout, j, dj);
-        x[j] = xn;
+        if (!mode.defer_iterate) x[j] = local_after(xj, xn, mode.pull, mode.rho);
       }
       m[j] = mj;
-      a_out[j] = xn;
+      if (!mode.defer_iterate) a_out[j] = xn;
     }
     const double tm = wave_sum(acc_m);
     const double tc = wave_sum(acc_c);
@@ -165,15 +198,70 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
   }
 }
 
+// Outer iterate of the norm-rescale variant, after the sweep has written m':
+//   x' = anchor - alpha*(m'*scale[s]),  scale[s] = min(1, phi/||m'||_s);
+//   anchor_out = x';  params = x' (or pulled towards it).
+// Same tile structure as the sweep; 8 (12 with params) bytes read and 4 (8)
+// written per coordinate.
+template <bool HAS_X>
+__global__ __launch_bounds__(kWave) void apply_iterate(
+    float* x, const float* a_in, float* a_out, const float* __restrict__ m,
+    const float* __restrict__ scale_tab, const int64_t* __restrict__ off, int S, int64_t n,
+    float alpha, SweepMode mode) {
+  const int64_t tile = blockIdx.x;
+  const int64_t base = tile * kSweepTile;
+  const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
+  const int lane = threadIdx.x;
+  const bool full = base + kSweepTile <= n;
+  const bool need_x = HAS_X && mode.pull;
+  float4 va, vm, vx = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  if (full) {
+    va = ld4_stream(a_in + base, lane);
+    vm = ld4_stream(m + base, lane);
+    if (need_x) vx = ld4_stream(x + base, lane);
+  }
+  const int s_lo = seg_of(off, S, base);
+
+  if (full && base + kSweepTile <= off[s_lo + 1]) {
+    const float scale = scale_tab[s_lo];
+    float xc[4], lc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float cm = comp(vm, e) * scale;
+      const float stepv = alpha * cm;
+      xc[e] = comp(va, e) - stepv;
+      lc[e] = local_after(comp(vx, e), xc[e], need_x, mode.rho);
+    }
+    if (HAS_X) st4_stream(x + base, kWave * 16, lane, make_float4(lc[0], lc[1], lc[2], lc[3]));
+    st4_stream(a_out + base, kWave * 16, lane, make_float4(xc[0], xc[1], xc[2], xc[3]));
+    return;
+  }
+
+  const int s_hi = seg_of(off, S, end - 1);
+  for (int s = s_lo; s <= s_hi; ++s) {
+    const int64_t lo = off[s] > base ? off[s] : base;
+    const int64_t hi = off[s + 1] < end ? off[s + 1] : end;
+    if (lo >= hi) continue;
+    const float scale = scale_tab[s];
+    for (int64_t j = lo + lane; j < hi; j += kWave) {
+      const float cm = m[j] * scale;
+      const float stepv = alpha * cm;
+      const float xn = a_in[j] - stepv;
+      if (HAS_X) x[j] = local_after(need_x ? x[j] : 0.0f, xn, need_x, mode.rho);
+      a_out[j] = xn;
+    }
+  }
+}
+
 // First outer round (Section 3.1: the gap/momentum/iterate lines are skipped):
 // delta_out = anchor - params; params = anchor_out = anchor.  Also leaves the
 // sums of Clip(m,phi)^2 and delta_out^2 per slot for the next round's gap.
 // Same tile structure as the sweep.
-template <bool HAS_X, bool BF16>
+template <bool HAS_X, int DT>
 __global__ __launch_bounds__(kWave) void first_round(
     float* x, const float* a_in, float* a_out, const float* __restrict__ m, void* dout,
     const int64_t* __restrict__ off, int S, int64_t n, float phi, SlotRec* __restrict__ slots) {
-  using IO = DeltaIO<BF16>;
+  using IO = DeltaIO<DT>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kSweepTile;
   const int64_t end = (base + kSweepTile < n) ? base + kSweepTile : n;
@@ -252,25 +340,34 @@ __global__ __launch_bounds__(kWave) void copy_f32(const float* __restrict__ src,
 
 // ---------------------------------------------------------------- launches
 
-template <int K, bool HAS_X, bool BF16>
+template <int NB, bool HAS_X, int DT>
 static hipError_t launch_sweep_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  // bf16 pseudo-gradients put half the bytes per stream in flight: cap like K/2 fp32 streams
-  const unsigned lds = throttle_lds_bytes(tuning().sweep_waves_per_cu[BF16 ? (K + 1) / 2 : K]);
+  // 16-bit pseudo-gradients put half the bytes per stream in flight: cap like NB/2 fp32 streams
+  const int streams = DT == kDeltaF32 ? NB : (NB + 1) / 2;
+  const unsigned lds = throttle_lds_bytes(g.waves_per_cu > 0 ? g.waves_per_cu
+                                                              : default_sweep_waves(streams));
   const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
-  hipLaunchKernelGGL((fused_sweep<K, HAS_X, BF16>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
-                     g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.slots);
+  hipLaunchKernelGGL((fused_sweep<NB, HAS_X, DT>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
+                     g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.mode, g.slots);
   return hipGetLastError();
 }
 
-template <int K>
+template <int NB>
 static hipError_t launch_sweep_k(bool has_x, const SweepArgs& g, hipStream_t st) {
-  if (g.bf16) return has_x ? launch_sweep_v<K, true, true>(g, st) : launch_sweep_v<K, false, true>(g, st);
-  return has_x ? launch_sweep_v<K, true, false>(g, st) : launch_sweep_v<K, false, false>(g, st);
+  if (g.dtype == kDeltaBF16)
+    return has_x ? launch_sweep_v<NB, true, kDeltaBF16>(g, st) : launch_sweep_v<NB, false, kDeltaBF16>(g, st);
+  if (g.dtype == kDeltaF16)
+    return has_x ? launch_sweep_v<NB, true, kDeltaF16>(g, st) : launch_sweep_v<NB, false, kDeltaF16>(g, st);
+  return has_x ? launch_sweep_v<NB, true, kDeltaF32>(g, st) : launch_sweep_v<NB, false, kDeltaF32>(g, st);
 }
 
-hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t st) {
-  switch (K) {
+hipError_t launch_fused_sweep(int nbuf, bool has_x, const SweepArgs& g, hipStream_t st) {
+  switch (nbuf) {
+    // no buffer at all: a single worker in the current-round order (fp32, fused form only)
+    case 0:
+      if (!has_x || g.dtype != kDeltaF32 || !g.mode.own_current) return hipErrorInvalidValue;
+      return launch_sweep_v<0, true, kDeltaF32>(g, st);
 #define CO2_CASE(k) case k: return launch_sweep_k<k>(has_x, g, st);
     CO2_CASE(1) CO2_CASE(2) CO2_CASE(3) CO2_CASE(4) CO2_CASE(5) CO2_CASE(6) CO2_CASE(7)
     CO2_CASE(8) CO2_CASE(9) CO2_CASE(10) CO2_CASE(11) CO2_CASE(12) CO2_CASE(13) CO2_CASE(14)
@@ -280,23 +377,39 @@ hipError_t launch_fused_sweep(int K, bool has_x, const SweepArgs& g, hipStream_t
   }
 }
 
-template <bool HAS_X, bool BF16>
+hipError_t launch_apply_iterate(bool has_x, const SweepArgs& g, const float* scale, hipStream_t st) {
+  const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
+  const unsigned lds = throttle_lds_bytes(default_sweep_waves(1));
+  if (has_x) {
+    hipLaunchKernelGGL((apply_iterate<true>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in, g.a_out,
+                       g.m, scale, g.off_dev, g.S, g.n, g.alpha, g.mode);
+  } else {
+    hipLaunchKernelGGL((apply_iterate<false>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in, g.a_out,
+                       g.m, scale, g.off_dev, g.S, g.n, g.alpha, g.mode);
+  }
+  return hipGetLastError();
+}
+
+template <bool HAS_X, int DT>
 static hipError_t launch_first_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  const unsigned lds = throttle_lds_bytes(tuning().sweep_waves_per_cu[1]);
-  hipLaunchKernelGGL((first_round<HAS_X, BF16>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
+  const unsigned lds = throttle_lds_bytes(default_sweep_waves(1));
+  hipLaunchKernelGGL((first_round<HAS_X, DT>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
                      g.a_out, g.m, g.dout, g.off_dev, g.S, g.n, g.phi, g.slots);
   return hipGetLastError();
 }
 
 hipError_t launch_first_round(bool has_x, const SweepArgs& g, hipStream_t st) {
-  if (g.bf16) return has_x ? launch_first_v<true, true>(g, st) : launch_first_v<false, true>(g, st);
-  return has_x ? launch_first_v<true, false>(g, st) : launch_first_v<false, false>(g, st);
+  if (g.dtype == kDeltaBF16)
+    return has_x ? launch_first_v<true, kDeltaBF16>(g, st) : launch_first_v<false, kDeltaBF16>(g, st);
+  if (g.dtype == kDeltaF16)
+    return has_x ? launch_first_v<true, kDeltaF16>(g, st) : launch_first_v<false, kDeltaF16>(g, st);
+  return has_x ? launch_first_v<true, kDeltaF32>(g, st) : launch_first_v<false, kDeltaF32>(g, st);
 }
 
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t st) {
   constexpr int64_t kTile = int64_t(kWave) * 16;
-  const unsigned lds = throttle_lds_bytes(tuning().copy_waves_per_cu);
+  const unsigned lds = throttle_lds_bytes(kCopyWavesPerCu);
   hipLaunchKernelGGL(copy_f32, dim3(static_cast<unsigned>((n + kTile - 1) / kTile)), dim3(kWave),
                      lds, st, src, dst, n);
   return hipGetLastError();

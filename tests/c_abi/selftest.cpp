@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "co2.h"
+#include "co2_layout.h"
 
 extern "C" int co2_oracle_outer_step_f32(int64_t n, int32_t S, const int64_t* seg_off, int32_t K,
                                          float alpha, float beta, float phi, float c, int32_t tau,

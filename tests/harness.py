@@ -56,7 +56,8 @@ class OuterStepHarness:
                  sample: Optional[Sequence[int]] = None, drift: str = "normal",
                  drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
                  momentum_std: float = 0.02, truth: bool = False, use_first_step_norm: bool = False,
-                 start_step: int = 0, bf16: bool = False):
+                 start_step: int = 0, bf16: bool = False, transport: Optional[str] = None,
+                 nonstale: bool = False, norm_clip: bool = False, pull_rho: float = 1.0):
         self.table = list(table)
         self.n, self.S = self.table[-1], len(self.table) - 1
         self.hp, self.dev, self.seed = hp, device, seed
@@ -67,12 +68,18 @@ class OuterStepHarness:
         self.x = torch.empty(n, **f32)
         self.a = torch.empty(n, **f32)
         self.m = torch.empty(n, **f32)
-        # pseudo-gradient buffers: fp32, or bf16 for the reduced-precision transport
-        self.bf16 = bf16
-        dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+        # pseudo-gradient buffers: fp32, or bf16 / fp16 for the reduced-precision transport
+        self.transport = transport or ("bf16" if bf16 else "f32")
+        self.bf16 = self.lowp = self.transport != "f32"       # 16-bit storage of the pseudo-gradients
+        # variants of the outer rule (fp32 transport only)
+        self.nonstale, self.norm_clip, self.pull_rho = nonstale, norm_clip, pull_rho
+        self.variant = nonstale or norm_clip or pull_rho != 1.0
+        assert not (self.variant and self.lowp)
+        dd = dict(dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.transport],
+                  device=device)
         self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]   # ping-pong: delta_out / deltas[0]
         self.peers = [torch.zeros(n, **dd) for _ in range(K - 1)]
-        self.scratch = torch.empty(n, **f32) if bf16 else None
+        self.scratch = torch.empty(n, **f32) if self.lowp else None
         self.lam = torch.empty(self.S, **f32)
         self.clipped = torch.full((self.S,), -1, dtype=torch.int64, device=device)
         self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
@@ -84,7 +91,7 @@ class OuterStepHarness:
             co2_inputs.fill_normal_(self.m, momentum_std, co2_inputs.seed_for(seed, 2))
         else:
             self.m.zero_()
-        self.t = start_step
+        self.t = self.t0 = start_step
 
         # ---- oracle side: sampled segments, compact table
         self.sample = list(range(self.S)) if sample is None else sorted(set(sample))
@@ -93,8 +100,8 @@ class OuterStepHarness:
         self.o_a = self.gather(self.a)
         self.o_m = self.gather(self.m)
         self.o_x = np.empty_like(self.o_a)
-        self.o_own = np.zeros(self.o_a.size, dtype=np.uint16 if bf16 else np.float32)
-        if start_step >= 1:
+        self.o_own = np.zeros(self.o_a.size, dtype=np.uint16 if self.lowp else np.float32)
+        if start_step >= 1 and not nonstale:
             # no earlier round has produced the worker's own previous
             # pseudo-gradient: draw it like a peer's
             self._fill_drift(self.own[start_step % 2], 99)
@@ -105,26 +112,27 @@ class OuterStepHarness:
     def gather(self, buf: torch.Tensor) -> np.ndarray:
         """Sampled segments of a device buffer as one host array (bf16 buffers
         come back as their uint16 bit patterns)."""
-        if buf.dtype == torch.bfloat16:
+        if buf.dtype in (torch.bfloat16, torch.float16):
             buf = buf.view(torch.int16)
         parts = [buf[self.table[s]:self.table[s + 1]] for s in self.sample]
         out = parts[0].cpu().numpy().copy() if len(parts) == 1 else torch.cat(parts).cpu().numpy()
         return out.view(np.uint16) if out.dtype == np.int16 else out
 
-    @staticmethod
-    def widen(bits: np.ndarray) -> np.ndarray:
-        """bf16 bit patterns -> the fp32 values they stand for (test-side, exact)."""
+    def widen(self, bits: np.ndarray) -> np.ndarray:
+        """16-bit patterns -> the fp32 values they stand for (test-side, exact)."""
+        if self.transport == "f16":
+            return bits.view(np.float16).astype(np.float32)
         return (bits.astype(np.uint32) << 16).view(np.float32)
 
     def _fill_drift(self, t: torch.Tensor, buffer_id: int):
         sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)
-        dst = self.scratch if t.dtype == torch.bfloat16 else t
+        dst = self.scratch if t.dtype != torch.float32 else t
         if self.drift == "student_t":
             co2_inputs.fill_student_t_(dst, self.drift_scale, self.drift_nu, sd)
         else:
             co2_inputs.fill_normal_(dst, self.drift_scale, sd)
         if dst is not t:
-            t.copy_(dst)                      # the sender's rounding to bf16 (input synthesis)
+            t.copy_(dst)                      # the sender's rounding to 16 bits (input synthesis)
 
     def step(self, flags: int = 0, split: bool = False, check: bool = True, events=None,
              full_check: bool = False):
@@ -133,15 +141,18 @@ class OuterStepHarness:
         that need no oracle (see _full_device_checks)."""
         hp, t = self.hp, self.t
         cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]   # cur: deltas[0]; nxt: delta_out
-        # inner loop stand-in: local params drift away from the anchor
-        noise = self.scratch if self.bf16 else nxt      # nxt is overwritten by delta_out anyway
+        # inner loop stand-in: local params drift away from where the last round left them
+        # (the anchor, or with an anchor pull the pulled local parameters)
+        noise = self.scratch if self.lowp else nxt      # nxt is overwritten by delta_out anyway
         self._fill_drift(noise, 100)
-        torch.add(self.a, noise, out=self.x)
+        pulled = self.pull_rho != 1.0 and t > self.t0
+        torch.add(self.x if pulled else self.a, noise, out=self.x)
         o_noise = self.gather(noise)
-        self.o_x = self.o_a + o_noise                   # same fp32 add as the line above
-        # peers' pseudo-gradients of the previous round (arrived through the all-reduce)
+        self.o_x = (self.o_x if pulled else self.o_a) + o_noise   # same fp32 add as the line above
+        # peers' pseudo-gradients: of the previous round (arrived through the all-reduce),
+        # or in the current-round order of this very round
         o_peers = []
-        if t >= 1:
+        if t >= 1 or self.nonstale:
             for k, pbuf in enumerate(self.peers):
                 self._fill_drift(pbuf, 200 + k)
                 o_peers.append(self.gather(pbuf))
@@ -154,11 +165,19 @@ class OuterStepHarness:
         if full_check:
             a_prev, x_prev = self.a.clone(), self.x.clone()
         ev_b, ev_e = events if events else (None, None)
+        if self.nonstale:
+            flags |= co2.CO2_FLAG_CURRENT_ROUND
+        if self.norm_clip:
+            flags |= co2.CO2_FLAG_NORM_CLIP
+        if self.pull_rho != 1.0:
+            flags |= co2.CO2_FLAG_ANCHOR_PULL
         p = co2.make_params(self.seg, hp.K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
-                            ev_b, ev_e, self.clipped)
-        deltas = [cur] + self.peers
+                            ev_b, ev_e, None if self.norm_clip else self.clipped, pull_rho=self.pull_rho)
+        # in the current-round order deltas[0] is not read: hand over no buffer at all
+        deltas = [None if self.nonstale else cur] + self.peers
         a_out = self.a
-        entry = co2.co2_outer_step_bf16 if self.bf16 else co2.co2_outer_step
+        entry = {"f32": co2.co2_outer_step, "bf16": co2.co2_outer_step_bf16,
+                 "f16": co2.co2_outer_step_f16}[self.transport]
         if split:
             # side-stream form: m and the next anchor only; the boundary work
             # (delta_out, params) is done by the caller
@@ -175,10 +194,10 @@ class OuterStepHarness:
         # state, so the bound below is a per-round statement)
         kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
                   tau=hp.tau, step=t)
-        if self.truth:
+        if self.truth and not self.variant:
             self.t_a, self.t_m = self.o_a.astype(np.float64), self.o_m.astype(np.float64)
             t_x = self.o_x.astype(np.float64)
-            val = self.widen if self.bf16 else (lambda v: v)
+            val = self.widen if self.lowp else (lambda v: v)
             t_d = ([val(self.o_own).astype(np.float64)] + [val(v).astype(np.float64) for v in o_peers]
                    if t >= 1 else None)
             self._truth_prev = (self.t_a.copy(), self.t_m.copy(), t_d)
@@ -189,9 +208,17 @@ class OuterStepHarness:
         # ---- oracle
         kw = dict(seg_off=self.otable, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
                   tau=hp.tau, step=t)
-        o_d = [self.o_own] + o_peers if t >= 1 else None
-        oracle_step = co2_oracle.outer_step_bf16 if self.bf16 else co2_oracle.outer_step_f32
-        out = oracle_step(x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d, first_step_norm=o_fsn, **kw)
+        if self.variant:
+            own = np.full(self.o_a.size, 1e3, np.float32) if self.nonstale else self.o_own   # poison: not read
+            o_d = [own] + o_peers if (t >= 1 or self.nonstale) else None
+            out = co2_oracle.outer_step_variant_f32(
+                x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d, first_step_norm=o_fsn,
+                nonstale=self.nonstale, norm_clip=self.norm_clip, pull_rho=self.pull_rho, **kw)
+        else:
+            o_d = [self.o_own] + o_peers if t >= 1 else None
+            oracle_step = {"f32": co2_oracle.outer_step_f32, "bf16": co2_oracle.outer_step_bf16,
+                           "f16": co2_oracle.outer_step_f16}[self.transport]
+            out = oracle_step(x=self.o_x, a=self.o_a, m=self.o_m, deltas=o_d, first_step_norm=o_fsn, **kw)
         self.o_own = out["dout"]
         self.last = out
         res = {}
@@ -207,10 +234,11 @@ class OuterStepHarness:
         """Properties of one round that hold for every coordinate, evaluated with
         plain torch reductions over the whole device buffers."""
         hp = self.hp
-        assert torch.equal(self.x, self.a), "params and anchor must both hold x_{t+1,0}"
+        if self.pull_rho == 1.0:
+            assert torch.equal(self.x, self.a), "params and anchor must both hold x_{t+1,0}"
         want_d = torch.sub(a_prev, x_prev)
-        if self.bf16:
-            want_d = want_d.to(torch.bfloat16)
+        if self.lowp:
+            want_d = want_d.to(dout.dtype)
         assert torch.equal(dout, want_d), "delta_out != anchor - params over the full buffer"
         del want_d, x_prev
         assert bool(torch.isfinite(self.m).all()) and bool(torch.isfinite(self.a).all())
@@ -229,24 +257,26 @@ class OuterStepHarness:
         res["params"] = assert_close(g_x, self.o_x, "params")
         res["anchor"] = assert_close(g_a, self.o_a, "anchor")
         res["momentum"] = assert_close(g_m, self.o_m, "momentum")
-        if self.bf16:
-            assert np.array_equal(g_d, self.o_own), "delta_out (bf16 bit patterns) differs"
+        if self.lowp:
+            assert np.array_equal(g_d, self.o_own), "delta_out (16-bit patterns) differs"
             res["delta_out"] = 0.0
         else:
             res["delta_out"] = assert_close(g_d, self.o_own, "delta_out")
         res["bit_exact"] = bool(np.array_equal(g_x, self.o_x) and np.array_equal(g_m, self.o_m)
                                 and np.array_equal(g_d, self.o_own) and np.array_equal(g_a, self.o_a))
         # per-segment count of clamped coordinates (integers: exact)
-        flag = np.abs(self.o_m) > np.float32(self.hp.phi) if self.last_step >= 1 else np.zeros(self.o_m.size, bool)
-        csum = np.concatenate([[0], np.cumsum(flag)])
-        want_c = csum[self.otable[1:]] - csum[self.otable[:-1]]
-        got_c = self.clipped[self.sample].cpu().numpy()
-        assert np.array_equal(got_c, want_c), "clipped-coordinate counts differ"
-        assert int(want_c.sum()) == self.last["nclipped"]
-        if self.last_step >= 1:
+        updated = self.last_step >= 1 or self.nonstale
+        if not self.norm_clip:
+            flag = np.abs(self.o_m) > np.float32(self.hp.phi) if updated else np.zeros(self.o_m.size, bool)
+            csum = np.concatenate([[0], np.cumsum(flag)])
+            want_c = csum[self.otable[1:]] - csum[self.otable[:-1]]
+            got_c = self.clipped[self.sample].cpu().numpy()
+            assert np.array_equal(got_c, want_c), "clipped-coordinate counts differ"
+            assert int(want_c.sum()) == self.last["nclipped"]
+        if updated:
             g_lam = self.lam[self.sample].cpu().numpy()
             res["lambda"] = assert_close(g_lam, self.last["lam"], "Lambda")
-        if self.truth and self.last_step >= 1:
+        if self.truth and self.last_step >= 1 and not self.variant:
             # against the all-fp64 evaluation: a sum is only accurate relative to
             # the size of its operands (beta*m and dbar/Lambda nearly cancel on a
             # few percent of coordinates)

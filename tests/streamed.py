@@ -9,8 +9,8 @@ several such groups can be handed to the (single-threaded, unchanged) oracle
 from several host threads at once.  Per chunk a worker thread
 
   1. copies the chunk of every INPUT both sides consume (the local drift, the
-     peers' pseudo-gradients -- all drawn by co2_inputs on the device) to pinned
-     host memory,
+     peers' pseudo-gradients -- all drawn by co2_inputs on the device) to host
+     memory (through small pinned bounce buffers),
   2. runs the oracle on it, in place on the oracle's own state,
   3. copies the chunk of every OUTPUT the device produced and compares it with
      the oracle's, element by element (bit equality first; where bits differ,
@@ -87,21 +87,25 @@ class SegmentChunks:
         self.order = sorted(range(len(self.chunks)), key=lambda q: -self.chunks[q].elems)
 
 
-# Pinned staging memory is slow to obtain and identical for every test of a
-# process: one pool, grown on demand, handed out as sets of equally sized buffers.
+# Staging memory.  The chunk-sized host arrays the oracle works on are ordinary
+# (pageable) numpy arrays, kept in one pool for the whole process and grown on
+# demand; device data reaches them through two small pinned bounce buffers per
+# worker thread (64 MiB each), so the amount of pinned memory stays at about a
+# gigabyte whatever the chunk size.
 _POOL = {"sets": [], "nbuf": 0, "nbytes": 0}
 _POOL_LOCK = threading.Lock()
+BOUNCE_BYTES = 64 << 20
 
 
 def staging_sets(nsets: int, nbuf: int, nbytes: int) -> "queue.Queue":
+    """A queue of `nsets` sets of `nbuf` uint8 host arrays of at least `nbytes` bytes."""
     with _POOL_LOCK:
         if _POOL["nbuf"] < nbuf or _POOL["nbytes"] < nbytes or len(_POOL["sets"]) < nsets:
             nb = max(nbuf, _POOL["nbuf"])
             by = max(nbytes, _POOL["nbytes"])
             ns = max(nsets, len(_POOL["sets"]))
             _POOL["sets"] = []                 # drop the old blocks before taking larger ones
-            _POOL["sets"] = [[torch.empty(by, dtype=torch.uint8, pin_memory=True) for _ in range(nb)]
-                             for _ in range(ns)]
+            _POOL["sets"] = [[np.zeros(by, dtype=np.uint8) for _ in range(nb)] for _ in range(ns)]
             _POOL["nbuf"], _POOL["nbytes"] = nb, by
         q: "queue.Queue" = queue.Queue()
         for s in _POOL["sets"][:nsets]:
@@ -110,30 +114,69 @@ def staging_sets(nsets: int, nbuf: int, nbytes: int) -> "queue.Queue":
 
 
 _TLS = threading.local()
+_BOUNCE_LOCK = threading.Lock()
+_BOUNCE_FREE: list = []          # pinned buffer pairs of threads that have ended
 
 
-def _copy_stream() -> torch.cuda.Stream:
-    if not hasattr(_TLS, "stream"):
-        _TLS.stream = torch.cuda.Stream()      # default priority
-    return _TLS.stream
+class _Lane:
+    """Per-thread copy stream and pinned bounce buffers (returned to a free list when
+    the thread object dies, so a new thread pool does not pin new memory)."""
+
+    def __init__(self):
+        with _BOUNCE_LOCK:
+            self.bounce = _BOUNCE_FREE.pop() if _BOUNCE_FREE else None
+        if self.bounce is None:
+            self.bounce = [torch.empty(BOUNCE_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+        self.stream = torch.cuda.Stream()      # default priority
+        self.done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def __del__(self):
+        with _BOUNCE_LOCK:
+            _BOUNCE_FREE.append(self.bounce)
 
 
-def stage(dev_buf: torch.Tensor, chunk: Chunk, pinned: torch.Tensor, ready: torch.cuda.Event) -> np.ndarray:
-    """Chunk of a device buffer -> numpy view of `pinned` (bf16 buffers come back
-    as their uint16 bit patterns).  Waits for `ready` on the device first."""
-    if dev_buf.dtype == torch.bfloat16:
+def _lane() -> _Lane:
+    if not hasattr(_TLS, "lane"):
+        _TLS.lane = _Lane()
+    return _TLS.lane
+
+
+def stage(dev_buf: torch.Tensor, chunk: Chunk, dest: np.ndarray, ready: torch.cuda.Event) -> np.ndarray:
+    """Chunk of a device buffer -> typed view of the host array `dest` (16-bit float
+    buffers come back as their uint16 bit patterns).  Waits for `ready` on the device
+    first.  The data travels in pieces through the thread's pinned bounce buffers: the
+    copy of one piece from the device overlaps the host copy of the previous one."""
+    if dev_buf.dtype in (torch.bfloat16, torch.float16):
         dev_buf = dev_buf.view(torch.int16)
-    host = pinned.view(dev_buf.dtype)[:chunk.elems]
-    s = _copy_stream()
-    with torch.cuda.stream(s):
-        s.wait_event(ready)
-        off = 0
-        for lo, hi in chunk.runs:
-            host[off:off + hi - lo].copy_(dev_buf[lo:hi], non_blocking=True)
-            off += hi - lo
-    s.synchronize()
-    out = host.numpy()
-    return out.view(np.uint16) if out.dtype == np.int16 else out
+    width = dev_buf.element_size()
+    np_dtype = {4: np.float32, 2: np.uint16}[width]
+    out = dest[:chunk.elems * width].view(np_dtype)
+    lane = _lane()
+    per = BOUNCE_BYTES // width
+    pieces = []
+    off = 0
+    for lo, hi in chunk.runs:
+        for p0 in range(lo, hi, per):
+            p1 = min(p0 + per, hi)
+            pieces.append((p0, p1, off))
+            off += p1 - p0
+    pending = None
+    with torch.cuda.stream(lane.stream):
+        lane.stream.wait_event(ready)
+        for i, (p0, p1, o) in enumerate(pieces):
+            b = lane.bounce[i % 2].view(dev_buf.dtype)[:p1 - p0]
+            b.copy_(dev_buf[p0:p1], non_blocking=True)
+            lane.done[i % 2].record(lane.stream)
+            if pending is not None:
+                pb, po, pe = pending
+                pe.synchronize()
+                out[po:po + pb.numel()] = pb.numpy().view(np_dtype)
+            pending = (b, o, lane.done[i % 2])
+    if pending is not None:
+        pb, po, pe = pending
+        pe.synchronize()
+        out[po:po + pb.numel()] = pb.numpy().view(np_dtype)
+    return out
 
 
 def for_each_chunk(chunks: SegmentChunks, fn, workers: int):
@@ -162,9 +205,11 @@ class StreamedOuterStepHarness:
                  sample: Optional[Sequence[int]] = None, drift: str = "normal",
                  drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
                  momentum_std: float = 0.02, start_step: int = 1, bf16: bool = False,
-                 chunk_elems: int = 1 << 26, workers: int = 8):
+                 transport: Optional[str] = None, chunk_elems: int = 1 << 26, workers: int = 8):
         self.table = [int(o) for o in table]
         self.n, self.S = self.table[-1], len(self.table) - 1
+        self.transport = transport or ("bf16" if bf16 else "f32")
+        bf16 = self.transport != "f32"                   # 16-bit storage of the pseudo-gradients
         self.hp, self.dev, self.seed, self.bf16 = hp, device, seed, bf16
         self.drift, self.drift_scale, self.drift_nu = drift, drift_scale, drift_nu
         self.workers = workers
@@ -174,7 +219,8 @@ class StreamedOuterStepHarness:
         self.ch = SegmentChunks(self.table, sample, chunk_elems)
         n, K = self.n, hp.K
         f32 = dict(dtype=torch.float32, device=device)
-        dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+        dd = dict(dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.transport],
+                  device=device)
         self.x, self.a, self.m = (torch.empty(n, **f32) for _ in range(3))
         self.noise = torch.empty(n, **f32)          # this round's local drift (an input of both sides)
         self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]
@@ -188,7 +234,7 @@ class StreamedOuterStepHarness:
         else:
             self.m.zero_()
         self.t = start_step
-        # staging: the K-1 peers + the drift as inputs; outputs reuse the same buffers afterwards
+        # staging: the K-1 peers + the drift as inputs; outputs reuse the same arrays afterwards
         self.sets = staging_sets(workers, max(K, 4), 4 * self.ch.max_chunk)
         # ---- oracle state over the compact index space
         nc = self.ch.n
@@ -214,7 +260,7 @@ class StreamedOuterStepHarness:
 
     def _fill_drift(self, t: torch.Tensor, buffer_id: int):
         sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)
-        dst = self.noise if t.dtype == torch.bfloat16 else t
+        dst = self.noise if t.dtype != torch.float32 else t
         if self.drift == "student_t":
             co2_inputs.fill_student_t_(dst, self.drift_scale, self.drift_nu, sd)
         else:
@@ -234,7 +280,8 @@ class StreamedOuterStepHarness:
         torch.add(self.a, self.noise, out=self.x)               # inner loop stand-in
         p = co2.make_params(self.seg, K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
                             clipped_out=self.clipped)
-        entry = co2.co2_outer_step_bf16 if self.bf16 else co2.co2_outer_step
+        entry = {"f32": co2.co2_outer_step, "bf16": co2.co2_outer_step_bf16,
+                 "f16": co2.co2_outer_step_f16}[self.transport]
         entry(p, self.x, self.a, self.a, self.m, [cur] + self.peers, nxt, None, self.lam, self.ws)
         ready = torch.cuda.Event()
         ready.record()
@@ -245,7 +292,8 @@ class StreamedOuterStepHarness:
         o_clip = np.zeros(S_c, dtype=np.int64)
         stats = {"bit_exact": True, "worst": 0.0}
         lock = threading.Lock()
-        oracle_step = co2_oracle.outer_step_bf16 if self.bf16 else co2_oracle.outer_step_f32
+        oracle_step = {"f32": co2_oracle.outer_step_f32, "bf16": co2_oracle.outer_step_bf16,
+                       "f16": co2_oracle.outer_step_f16}[self.transport]
         phi32 = np.float32(hp.phi)
 
         def work(c: Chunk):
@@ -266,7 +314,7 @@ class StreamedOuterStepHarness:
                 same_or_close(stage(self.m, c, st[1], ready), self.o_m[sl], "momentum", local)
                 g_d = stage(nxt, c, st[2], ready)
                 if self.bf16:
-                    assert np.array_equal(g_d, out["dout"]), "delta_out (bf16 bit patterns) differs"
+                    assert np.array_equal(g_d, out["dout"]), "delta_out (16-bit patterns) differs"
                 else:
                     same_or_close(g_d, out["dout"], "delta_out", local)
                 o_lam[c.i0:c.i1] = out["lam"]

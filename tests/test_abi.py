@@ -12,10 +12,11 @@ import pytest
 import paper_2401_16265_amd as co2
 
 HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "co2.h")
+LAYOUT_HEADER = os.path.join(os.path.dirname(HEADER), "co2_layout.h")
 
 
 def declared_functions():
-    src = open(HEADER).read()
+    src = open(HEADER).read() + open(LAYOUT_HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(co2_[a-z0-9_]+)\s*\(", src)))
 
@@ -37,7 +38,7 @@ def test_params_struct_layout_matches_header():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"([A-Za-z_][A-Za-z0-9_]*)\s*;", body)
     assert fields == [f[0] for f in co2.Co2Params._fields_]
-    assert C.sizeof(co2.Co2Params) == 8 + 4 + 4 + 8 + 8 + 16 + 4 + 4 + 8 + 8 + 8 + 8
+    assert C.sizeof(co2.Co2Params) == 8 + 4 + 4 + 8 + 8 + 16 + 4 + 4 + 8 + 8 + 8 + 8 + 4 + 4
 
 
 def test_strerror_and_workspace_bytes():
@@ -80,7 +81,10 @@ def _call(p, params=_fake(0), anchor=_fake(1), anchor_out=_fake(1), momentum=_fa
 @pytest.mark.parametrize("bad", [
     dict(K=0), dict(K=17), dict(tau=0), dict(step=-1), dict(beta=1.0), dict(beta=-0.1),
     dict(clip_phi=0.0), dict(clip_phi=-1.0), dict(clip_phi=float("nan")), dict(penalty_c=-1.0),
-    dict(alpha=float("inf")), dict(alpha=float("nan")), dict(flags=2), dict(seg_off_dev=None),
+    dict(alpha=float("inf")), dict(alpha=float("nan")), dict(flags=16), dict(seg_off_dev=None),
+    dict(sweep_waves_per_cu=-1), dict(sweep_waves_per_cu=33),
+    dict(flags=4, pull_rho=0.0), dict(flags=4, pull_rho=1.5), dict(flags=4, pull_rho=float("nan")),
+    dict(flags=2, penalty_c=1.0),                 # current-round order with a penalty needs first-step norms
     dict(S=0), dict(n=0), dict(n=4095), dict(flags=1, step=0),
 ])
 def test_outer_step_rejects_bad_hyperparameters(bad):
@@ -209,13 +213,20 @@ def test_header_is_plain_c(tmp_path):
     """include/co2.h must be usable from C (no C++-only constructs, no HIP/torch types)."""
     import subprocess
     src = tmp_path / "use_header.c"
-    src.write_text('#include "co2.h"\n'
-                   "int main(void) { co2_params p; p.n = 1; (void)p; "
+    src.write_text('#include "co2.h"\n#include "co2_layout.h"\n'
+                   "int main(void) { co2_params p; co2_buffer_set* b = 0; p.n = 1; (void)p; (void)b; "
                    "return (int)co2_workspace_bytes(0, 0, 0) + (co2_strerror(0) == 0); }\n")
     inc = os.path.dirname(HEADER)
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
                     "-o", str(tmp_path / "use_header.o")], check=True)
-    text = open(HEADER).read()
+    text = open(HEADER).read() + open(LAYOUT_HEADER).read()
+    # the compute header declares nothing that allocates, and the library has no hidden
+    # configuration channel: no source file reads the environment
+    plain = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    assert "create" not in plain and "destroy" not in plain
+    csrc = os.path.join(os.path.dirname(co2.__file__), "csrc")
+    for f in os.listdir(csrc):
+        assert "getenv" not in open(os.path.join(csrc, f)).read(), f
     for forbidden in ("torch", "hipStream_t ", "#include <hip", "at::Tensor"):
         assert forbidden not in text.replace("a hipStream_t;", "")
 
@@ -238,5 +249,5 @@ def test_buffer_set_rejects_bad_arguments():
     assert L.co2_buffer_set_create(1, one, 3 * mib, out, C.byref(handle)) == co2.CO2_EINVAL
     assert L.co2_buffer_set_destroy(None) == co2.CO2_EINVAL
     assert not handle.value
-    src = open(HEADER).read()
+    src = open(LAYOUT_HEADER).read()
     assert int(re.search(r"#define CO2_MAX_BUFFER_SET (\d+)", src).group(1)) == co2.CO2_MAX_BUFFER_SET

@@ -305,3 +305,92 @@ def test_overlapped_rounds_350m(dev):
         lam_max = max(lam_max, float(ow.lam.max()))
         print(f"  350m round {t}: {res} lam_max={float(ow.lam.max()):.4f}", flush=True)
     assert lam_max > 1.0
+
+
+# ------------------------------------------------------------------ the race surface of the schedule
+def _small_setup(dev, seed):
+    table = co2_inputs.gpt_table(layers=2, d=65, ffn=257, vocab=1001, ctx=33)
+    seg = co2.SegmentTable(table, dev)
+    n, K, tau = seg.n, 4, 3
+    f32 = dict(dtype=torch.float32, device=dev)
+    init = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(seed, 1))
+    mk = lambda: CO2Worker(seg, K, tau, 1.0, 0.9, 1e-3, 1.0, AdamWConfig(**HP), dev, init)  # noqa: E731
+    grads = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)]
+
+    def inputs(t, workers):
+        for k, g in enumerate(grads):
+            co2_inputs.fill_bf16_normal_(g, 1e-3, co2_inputs.seed_for(seed, 10 + k, t))
+        for j in range(K - 1):
+            co2_inputs.fill_normal_(workers[0].peers[j], 1e-3, co2_inputs.seed_for(seed, 200 + j, t))
+            for w in workers[1:]:
+                w.peers[j].copy_(workers[0].peers[j])
+    return table, mk, grads, inputs, init
+
+
+def test_delayed_side_stream_still_gives_the_serial_bits(dev):
+    """The wait of Algorithm 1 (the outer update of round t must have finished before
+    round t+1 starts from its result): the side stream is held up by a queue of large
+    copies ahead of every outer update, so the main stream reaches the round boundary
+    long before the update exists and must block on the event.  Every round must still
+    equal the serial order bit for bit, and the oracle."""
+    table, mk, grads, inputs, init = _small_setup(dev, seed=71)
+    w_ov, w_se = mk(), mk()
+    ow = OracleWorker(table, list(range(len(table) - 1)), 4, 3, 1.0, 0.9, 1e-3, 1.0, init)
+    big = 1 << 27                                                  # 512 MiB per buffer: ~0.2 ms per copy
+    src, dst = torch.zeros(big, device=dev), torch.empty(big, device=dev)
+    lag = []
+    for t in range(5):
+        inputs(t, [w_ov, w_se])
+        w_ov.side.wait_stream(w_ov.main)                           # the copies start after the inputs exist
+        for _ in range(40):                                        # ~10 ms of work ahead of the outer update
+            co2.co2_copy_f32(src, dst, big, stream=w_ov.side)
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t0.record(w_ov.main)
+        w_ov.round_overlapped(grads)
+        t1.record(w_ov.main)                                       # after main's wait on the side event
+        w_se.round_serial(grads)
+        ow.round(grads, w_ov.peers)
+        torch.cuda.synchronize()
+        lag.append(t0.elapsed_time(t1))
+        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam"):
+            assert torch.equal(getattr(w_ov, name), getattr(w_se, name)), f"round {t}: {name}: delayed != serial"
+        for i in range(2):
+            assert torch.equal(w_ov.anchor[i], w_se.anchor[i]) and torch.equal(w_ov.own[i], w_se.own[i])
+        assert_close(ow.gather(w_ov.params), ow.params, "params")
+        assert_close(ow.gather(w_ov.anchor[(t + 1) % 2]), ow.anchor, "next anchor")
+    # the main stream really waited: its round took as long as the queue on the side stream
+    assert min(lag) > 3.0, f"main stream did not block on the delayed update: {lag} ms"
+
+
+def test_misordered_schedule_is_caught(dev):
+    """What the events protect against: a schedule that starts round t+1's local steps
+    BEFORE round t's outer update has produced the anchor they start from (one stream,
+    so the wrong order is deterministic).  It must NOT reproduce the oracle, while the
+    right order on the same inputs does: the parity check is sensitive to exactly the
+    mistake a missing wait would make."""
+    table, mk, grads, inputs, init = _small_setup(dev, seed=72)
+    good, bad = mk(), mk()
+    bad.anchor[1].copy_(bad.anchor[0])                             # no uninitialised reads in the wrong order
+    ow = OracleWorker(table, list(range(len(table) - 1)), 4, 3, 1.0, 0.9, 1e-3, 1.0, init)
+
+    def round_misordered(w):
+        w._inner_loop(grads, w.main)                               # reads anchor[t % 2] too early ...
+        if w.t >= 1:
+            w.t -= 1
+            w._outer_update(w.main, carried=False)                 # ... round t-1's update only arrives now
+            w.t += 1
+        w.t += 1
+
+    differs = []
+    for t in range(5):
+        inputs(t, [good, bad])
+        good.round_serial(grads)
+        round_misordered(bad)
+        ow.round(grads, good.peers)
+        torch.cuda.synchronize()
+        assert_close(ow.gather(good.params), ow.params, "params (right order)")
+        differs.append(not np.array_equal(ow.gather(bad.params), ow.params))
+    # rounds 0 and 1 cannot tell: round 0 has no earlier update, and the first round's
+    # update leaves the anchor where it was (Section 3.1)
+    assert differs[:2] == [False, False], differs
+    assert all(differs[2:]), f"the wrong order went unnoticed: {differs}"

@@ -45,7 +45,7 @@ def parse():
                          "previous round's sweep); two_pass: separate norm pass every round")
     ap.add_argument("--workload", default="1p3b")
     ap.add_argument("--K", type=int, default=0, help="override the workload's worker count")
-    ap.add_argument("--deltas", choices=["f32", "bf16"], default="f32",
+    ap.add_argument("--deltas", choices=["f32", "bf16", "f16"], default="f32",
                     help="storage type of the K pseudo-gradient buffers and of delta_out "
                          "(bf16: reduced-precision transport, co2_outer_step_bf16)")
     ap.add_argument("--separate-allocations", action="store_true",
@@ -57,11 +57,18 @@ def parse():
                          "layout is kept.  0 = no compaction, no search: the first plain allocation "
                          "as it comes")
     ap.add_argument("--piece-major", action="store_true",
-                    help="also try two piece-major buffer sets (co2_buffer_set_create) as candidates")
+                    help="also try piece-major buffer sets (co2_buffer_set_create) as candidates")
+    ap.add_argument("--piece-mib", default="",
+                    help="comma-separated piece sizes in MiB for --piece-major (default: 1024,512)")
     ap.add_argument("--hip-graph", action="store_true",
                     help="also capture two consecutive rounds into a HIP graph and time its replays; "
                          "value and ms_per_step then come from the replays (launch-bound small "
                          "workloads), the roofline still from the eager launches")
+    ap.add_argument("--sweep-waves", type=int, default=0,
+                    help="co2_params.sweep_waves_per_cu for the timed launches (0 = the library's default)")
+    ap.add_argument("--side-waves", type=int, default=-1,
+                    help="350m_overlap only: sweep_waves_per_cu of the side-stream outer update "
+                         "(-1 = the schedule's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -187,6 +194,8 @@ def overlap_bench(args):
     res = {}
     for mode in ("serial", "overlapped"):
         w = CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**hp), dev, init)
+        if args.side_waves >= 0:
+            w.side_waves = args.side_waves
         for j, pb in enumerate(w.peers):
             co2_inputs.fill_normal_(pb, cfg.drift_scale, co2_inputs.seed_for(cfg.seed, 200 + j))
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 1)]
@@ -201,6 +210,7 @@ def overlap_bench(args):
         per = [evs[r].elapsed_time(evs[r + 1]) for r in range(rounds)]
         res[mode] = {"median_ms": statistics.median(per[10:]), "min_ms": min(per[10:]),
                      "wall_ms_per_round": wall * 1e3 / rounds}
+        w_side_waves = w.side_waves
         del w
         torch.cuda.empty_cache()
     bytes_round = (26 * tau + 8 + 4) * n + (16 + 4 * K) * n   # AdamW steps (+dout, +anchor read) + split outer update
@@ -209,6 +219,7 @@ def overlap_bench(args):
            "warmup": 10, "ms_per_step": res["overlapped"]["median_ms"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{cfg.name}: n={n}, K={K}, tau={tau}, bf16 grads, fp32 master",
+                      "side_stream_sweep_waves_per_cu": w_side_waves,
                       "compacted_gib": round(compacted / 2**30, 1)},
            "serial": res["serial"], "overlapped": res["overlapped"],
            "overlap_speedup": res["serial"]["median_ms"] / res["overlapped"]["median_ms"],
@@ -249,13 +260,15 @@ def main():
     # to each other in HBM (up to 10 % between allocations, 3 % between gaps), so the
     # allocation and the gap are chosen by timing the sweep itself on a few candidates
     # before anything is initialised (paper_2401_16265_amd/placement.py).
-    bf16 = args.deltas == "bf16"
-    dd = dict(dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
+    bf16 = args.deltas != "f32"                     # 16-bit storage of the pseudo-gradients
+    dd = dict(dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.deltas],
+              device=dev)
     lam = torch.empty(S, **f32)
     ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     carried = args.form == "carried"
-    entry = co2.co2_outer_step_bf16 if bf16 else co2.co2_outer_step
+    entry = {"f32": co2.co2_outer_step, "bf16": co2.co2_outer_step_bf16,
+             "f16": co2.co2_outer_step_f16}[args.deltas]
 
     def typed(views):
         a, m, x = (v.view(torch.float32) for v in views[:3])
@@ -268,7 +281,8 @@ def main():
         cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
         flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
-                            ev[0] if ev else None, ev[1] if ev else None, clipped)
+                            ev[0] if ev else None, ev[1] if ev else None, clipped,
+                            sweep_waves_per_cu=args.sweep_waves)
         entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=on or stream)
 
     def probe(views, reps=3):
@@ -294,14 +308,16 @@ def main():
         search = args.placement_candidates > 0
         placement = pl.choose_placement(sizes, probe if search else None, dev,
                                         candidates=args.placement_candidates, probe_first=search,
-                                        pieces=pl.DEFAULT_PIECES if args.piece_major else (),
+                                        compact=search,     # the bench has the GPU to itself
+                                        pieces=(tuple(int(v) << 20 for v in args.piece_mib.split(",")) if args.piece_mib
+                                                else pl.DEFAULT_PIECES) if args.piece_major else (),
                                         gaps=pl.DEFAULT_GAPS if search else (pl.PAGE,))
         a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"
 
     def drift(t, bid, rnd=0):
         sd = co2_inputs.seed_for(cfg.seed, bid, rnd)
-        dst = x if t.dtype == torch.bfloat16 else t       # x doubles as fp32 scratch here
+        dst = x if t.dtype != torch.float32 else t        # x doubles as fp32 scratch here
         if student:
             co2_inputs.fill_student_t_(dst, cfg.drift_scale, cfg.drift_nu, sd)
         else:

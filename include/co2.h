@@ -35,11 +35,12 @@
  *     the sweep streams all of them at once and runs 2-5 % faster than over
  *     buffers the allocator has scattered.  Which physical pages back that
  *     allocation moves the sweep's duration by up to 10 % more and stays fixed
- *     for the allocation's life.  On a device whose memory has been through
- *     many allocate/free cycles it pays to allocate nearly all free memory in
- *     one piece and free it again first (the driver then merges its free
- *     blocks), and a long-running caller can time the sweep on a few candidate
- *     allocations held together and keep the fastest.
+ *     for the allocation's life.  A long-running caller can time the sweep on
+ *     a few candidate allocations held together and keep the fastest; on a
+ *     device that the process has to itself and whose memory has been through
+ *     many allocate/free cycles it also pays to allocate nearly all free
+ *     memory in one piece and free it again first (the driver then merges its
+ *     free blocks; never do this on a device shared with other processes).
  *   - Return value: CO2_OK or a negative error code.  Arguments are checked
  *     before the first launch: on CO2_EINVAL or CO2_EWORKSPACE nothing has
  *     been enqueued and no buffer has been touched.  CO2_EHIP reports a HIP

@@ -72,6 +72,8 @@ def compact_device_memory(device, headroom: int = 3 << 30) -> int:
     makes the driver do that merge, and what is freed afterwards is one block
     again.  Measured: plain allocations that probed at 12.5-13.4 ms before this
     call probed at 11.9-12.0 ms (the first and third of three) right after it.
+    Only for a device this process has to itself: for a moment nearly all free memory
+    is taken, and another process allocating at that instant would fail.
     Returns the number of bytes that were taken (0 if nothing could be)."""
     if torch.device(device).type != "cuda":
         return 0
@@ -129,12 +131,14 @@ class Placement:
 def choose_placement(sizes: Sequence[int], probe: Optional[Callable[[List[torch.Tensor]], float]],
                      device, candidates: int = 4, gaps: Sequence[int] = DEFAULT_GAPS,
                      pieces: Sequence[int] = (), reserve_bytes: int = 4 << 30,
-                     spacer_bytes: int = 192 << 20, buffer_set=None, compact: bool = True,
+                     spacer_bytes: int = 192 << 20, buffer_set=None, compact: bool = False,
                      probe_first: bool = False) -> Placement:
     """Allocate buffers of `sizes` bytes where `probe` runs fastest.
 
     With `probe` None this is one plain allocation with the first gap.  Otherwise:
-    compact_device_memory() first (unless `compact` is False), then
+    compact_device_memory() first if `compact` is set (opt-in: it takes nearly all free
+    device memory for a moment, which is only safe on a device this process has to
+    itself), then
     up to `candidates` plain allocations, then one piece-major buffer set per
     entry of `pieces` (`buffer_set(sizes, piece, device)` -> object with .views
     and .close(); default: the library's BufferSet), each zero-filled and timed

@@ -83,6 +83,9 @@ class CO2Worker:
         self.ev_side = torch.cuda.Event()
         self.t = 0            # outer round index
         self.adam_k = 0       # AdamW step count (bias correction)
+        # Resident-wavefront cap of the side-stream sweep while it shares the GPU with
+        # the AdamW steps (co2_params.sweep_waves_per_cu; 0 = the sweep's stand-alone default)
+        self.side_waves = 0
 
     # ------------------------------------------------------------------ pieces
     def _inner_loop(self, grads: List[torch.Tensor], stream):
@@ -107,7 +110,7 @@ class CO2Worker:
         t = self.t
         flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 1) else 0
         p = co2.make_params(self.table, self.K, self.alpha, self.beta, self.phi, self.c, self.tau,
-                            t, flags)
+                            t, flags, sweep_waves_per_cu=self.side_waves if stream is self.side else 0)
         deltas = [self.own[(t - 1) % 2]] + self.peers          # round t-1's pseudo-gradients
         co2.co2_outer_step(p, None, self.anchor[t % 2], self.anchor[(t + 1) % 2], self.momentum,
                            deltas, None, self.fsn[(t - 1) % 2] if t >= 1 else None, self.lam,

@@ -64,6 +64,9 @@ def parse():
                     help="also capture two consecutive rounds into a HIP graph and time its replays; "
                          "value and ms_per_step then come from the replays (launch-bound small "
                          "workloads), the roofline still from the eager launches")
+    ap.add_argument("--variant", default="",
+                    help="comma-separated variant switches of the outer rule for the timed launches: "
+                         "current_round, anchor_pull, norm_clip (fp32 transport only; not the headline)")
     ap.add_argument("--sweep-waves", type=int, default=0,
                     help="co2_params.sweep_waves_per_cu for the timed launches (0 = the library's default)")
     ap.add_argument("--side-waves", type=int, default=-1,
@@ -275,15 +278,25 @@ def main():
         ds = [v.view(dd["dtype"]) for v in views[3:]]
         return a, m, x, ds[:2], ds[2:]
 
+    variant = [v for v in args.variant.split(",") if v]
+    vflags = 0
+    for v in variant:
+        vflags |= {"current_round": co2.CO2_FLAG_CURRENT_ROUND, "anchor_pull": co2.CO2_FLAG_ANCHOR_PULL,
+                   "norm_clip": co2.CO2_FLAG_NORM_CLIP}[v]
+    # the current-round order keeps no previous own pseudo-gradient: Eq. 3's denominator comes
+    # from first-inner-step norms (synthetic here: the drift scale)
+    fsn = torch.full((S,), cfg.drift_scale, **f32) if "current_round" in variant else None
+
     def launch(bufs, t, ev=None, clipped=None, on=None):
         """One outer step of round t on stream `on` (default: the current stream)."""
         a, m, x, own, peers = bufs
         cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
-        flags = co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0
+        flags = (co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0) | vflags
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
-                            ev[0] if ev else None, ev[1] if ev else None, clipped,
-                            sweep_waves_per_cu=args.sweep_waves)
-        entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws, stream=on or stream)
+                            ev[0] if ev else None, ev[1] if ev else None,
+                            None if "norm_clip" in variant else clipped,
+                            pull_rho=0.5, sweep_waves_per_cu=args.sweep_waves)
+        entry(p, x, a, a, m, [cur] + peers, nxt, fsn, lam, ws, stream=on or stream)
 
     def probe(views, reps=3):
         """Median duration (ms) of the sweep kernel over `reps` launches on these buffers."""
@@ -394,6 +407,10 @@ def main():
     sweep_times = [b.elapsed_ms(e) for b, e in sweep_ev]
     sweep_ms = sum(sweep_times) / len(sweep_times)
     per_elem = (26 + 2 * K) if bf16 else (28 + 4 * K)   # algorithmic bytes per coordinate, one sweep
+    if "current_round" in variant:
+        per_elem -= 4                                    # deltas[0] is not read
+    if "norm_clip" in variant:
+        per_elem -= 8                                    # params and anchor are written by the second kernel
     sweep_bytes = per_elem * n
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
     lam_all = torch.stack(lam_hist)
@@ -422,6 +439,7 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} fp32 params, S={S} segments, K={K} worker "
                                f"buffers, {cfg.drift} drift, beta={cfg.beta} phi={cfg.phi} "
                                f"c={cfg.c}", "form": args.form, "deltas": args.deltas, "launch": launch_mode,
+                   "variant": variant or "none (Algorithm 1)",
                    "inputs": "local params and the K-1 peers' pseudo-gradients redrawn before every round, "
                              "untimed; the worker's own pseudo-gradient is the previous round's delta_out",
                    "timing": {"per": "round, HIP events on the launch stream around all kernels of the step",

@@ -64,6 +64,7 @@ constexpr int kNormWavesTwoBuffers = 8;
 constexpr int kAdamWavesPerCu = 7;
 constexpr int kAdamWavesWithAnchor = 5;   // the step that also reads the anchor and writes delta_out
 constexpr int kCopyWavesPerCu = 7;
+constexpr int kApplyWavesPerCu = 16;      // deferred outer iterate: 2-3 KB of loads per wavefront
 // Records `e` as this thread's most recent HIP error (what co2_last_hip_error() returns).
 void note_hip_error(hipError_t e);
 // Dynamic LDS bytes to request per single-wavefront workgroup so that at most

@@ -379,7 +379,7 @@ hipError_t launch_fused_sweep(int nbuf, bool has_x, const SweepArgs& g, hipStrea
 
 hipError_t launch_apply_iterate(bool has_x, const SweepArgs& g, const float* scale, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  const unsigned lds = throttle_lds_bytes(default_sweep_waves(1));
+  const unsigned lds = throttle_lds_bytes(kApplyWavesPerCu);
   if (has_x) {
     hipLaunchKernelGGL((apply_iterate<true>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in, g.a_out,
                        g.m, scale, g.off_dev, g.S, g.n, g.alpha, g.mode);

@@ -48,18 +48,19 @@ def parse():
     ap.add_argument("--deltas", choices=["f32", "bf16", "f16"], default="f32",
                     help="storage type of the K pseudo-gradient buffers and of delta_out "
                          "(bf16: reduced-precision transport, co2_outer_step_bf16)")
-    ap.add_argument("--separate-allocations", action="store_true",
-                    help="allocate every buffer on its own instead of carving all of them out of "
-                         "one device allocation (the layout the library recommends)")
+    ap.add_argument("--layout", choices=["piece-major", "search", "first", "separate"], default="piece-major",
+                    help="where the flat buffers live.  piece-major (default): one co2_buffer_set with "
+                         "64 MiB pieces, made after the free device memory has been compacted; no "
+                         "selection by timing (a plain first allocation is timed beforehand only to be "
+                         "reported).  search: compaction, then the sweep is timed on "
+                         "--placement-candidates plain allocations x three gaps (plus buffer sets of the "
+                         "--piece-mib sizes) and the fastest layout is kept.  first: one plain allocation "
+                         "as the device hands it out.  separate: one allocation per buffer")
     ap.add_argument("--placement-candidates", type=int, default=3,
-                    help="plain device allocations tried for the buffers after the free device memory "
-                         "has been compacted; the sweep is timed on each candidate and the fastest "
-                         "layout is kept.  0 = no compaction, no search: the first plain allocation "
-                         "as it comes")
-    ap.add_argument("--piece-major", action="store_true",
-                    help="also try piece-major buffer sets (co2_buffer_set_create) as candidates")
+                    help="--layout search: plain device allocations tried")
     ap.add_argument("--piece-mib", default="",
-                    help="comma-separated piece sizes in MiB for --piece-major (default: 1024,512)")
+                    help="comma-separated piece sizes in MiB of the buffer sets (piece-major: the first "
+                         "one, default 64; search: all of them as extra candidates, default none)")
     ap.add_argument("--hip-graph", action="store_true",
                     help="also capture two consecutive rounds into a HIP graph and time its replays; "
                          "value and ms_per_step then come from the replays (launch-bound small "
@@ -310,7 +311,8 @@ def main():
         return sorted(b.elapsed_ms(e) for b, e in evs)[reps // 2]
 
     placement = None
-    if args.separate_allocations:
+    layout = args.layout
+    if layout == "separate":
         a = torch.empty(n, **f32); m = torch.empty(n, **f32); x = torch.empty(n, **f32)
         own = [torch.empty(n, **dd), torch.empty(n, **dd)]
         peers = [torch.empty(n, **dd) for _ in range(K - 1)]
@@ -318,13 +320,23 @@ def main():
         from paper_2401_16265_amd import placement as pl
         dbytes = n * (2 if bf16 else 4)
         sizes = [4 * n] * 3 + [dbytes] * (K + 1)
-        search = args.placement_candidates > 0
-        placement = pl.choose_placement(sizes, probe if search else None, dev,
-                                        candidates=args.placement_candidates, probe_first=search,
-                                        compact=search,     # the bench has the GPU to itself
-                                        pieces=(tuple(int(v) << 20 for v in args.piece_mib.split(",")) if args.piece_mib
-                                                else pl.DEFAULT_PIECES) if args.piece_major else (),
-                                        gaps=pl.DEFAULT_GAPS if search else (pl.PAGE,))
+        pieces = tuple(int(v) << 20 for v in args.piece_mib.split(",")) if args.piece_mib else ()
+        if layout == "piece-major":
+            # The recommended layout, taken as it comes: no candidate is timed against another.
+            # (The bench has the GPU to itself, so it may compact the free memory first.)
+            try:
+                placement = pl.choose_placement(sizes, probe, dev, candidates=0, probe_first=True,
+                                                compact=True, pieces=(pieces or pl.DEFAULT_PIECES)[:1])
+            except RuntimeError as exc:               # no virtual-memory support, or no room
+                print(f"bench.py: piece-major buffer set unavailable ({exc}); falling back to "
+                      "--layout search", file=sys.stderr)
+                layout = "search"
+        if layout == "search":
+            placement = pl.choose_placement(sizes, probe, dev, candidates=max(1, args.placement_candidates),
+                                            probe_first=True, compact=True, pieces=pieces,
+                                            gaps=pl.DEFAULT_GAPS)
+        elif layout == "first":
+            placement = pl.choose_placement(sizes, None, dev, gaps=(pl.PAGE,))
         a, m, x, own, peers = typed(placement.views)
     student = cfg.drift == "student_t"
 
@@ -448,9 +460,9 @@ def main():
                               "wall_s_including_input_generation": wall},
                    "lambda_min": lam_min, "lambda_max": lam_max,
                    "clipped_coordinates_last_timed_step": clipped_count,
+                   "layout": layout,
                    "placement": ("separate allocations" if placement is None else
-                                 placement.report() if args.placement_candidates > 0 else
-                                 "first allocation"),
+                                 placement.report() if layout != "first" else "first allocation"),
                    "step_gbps_algorithmic": (per_elem + (0 if carried else (6 if bf16 else 8))) * n
                                             / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -29,18 +29,21 @@
  *     tells the first round from the later ones, so two captured steady-state
  *     rounds -- the two halves of a delta_out ping-pong -- can be replayed for
  *     the rest of a run.
- *   - Every DEVICE buffer must be 16-byte aligned.  Layout advice: carve the
- *     flat buffers of one worker (params, anchor, momentum, the K pseudo-
- *     gradient buffers, delta_out) out of ONE device allocation, 4 KiB aligned;
- *     the sweep streams all of them at once and runs 2-5 % faster than over
- *     buffers the allocator has scattered.  Which physical pages back that
- *     allocation moves the sweep's duration by up to 10 % more and stays fixed
- *     for the allocation's life.  A long-running caller can time the sweep on
- *     a few candidate allocations held together and keep the fastest; on a
- *     device that the process has to itself and whose memory has been through
- *     many allocate/free cycles it also pays to allocate nearly all free
- *     memory in one piece and free it again first (the driver then merges its
- *     free blocks; never do this on a device shared with other processes).
+ *   - Every DEVICE buffer must be 16-byte aligned.  Layout advice: the sweep
+ *     streams all flat buffers of one worker (params, anchor, momentum, the K
+ *     pseudo-gradient buffers, delta_out) in lock step, and on MI355X its
+ *     duration depends on which physical pages lie behind them, by up to 10 %
+ *     between otherwise identical plain allocations (fixed for an allocation's
+ *     life).  A buffer set of co2_layout.h with its default 64 MiB pieces has
+ *     measured fast every time (84 % of the HBM peak at K = 4 ... 16, where
+ *     plain allocations gave 77-84 %); failing that, carve the buffers out of
+ *     ONE device allocation, 4 KiB aligned (2-5 % faster than scattered
+ *     buffers), and a long-running caller can time the sweep on a few
+ *     candidate allocations held together and keep the fastest.  On a device
+ *     that the process has to itself and whose memory has been through many
+ *     allocate/free cycles it also pays to allocate nearly all free memory in
+ *     one piece and free it again first (the driver then merges its free
+ *     blocks; never do this on a device shared with other processes).
  *   - Return value: CO2_OK or a negative error code.  Arguments are checked
  *     before the first launch: on CO2_EINVAL or CO2_EWORKSPACE nothing has
  *     been enqueued and no buffer has been touched.  CO2_EHIP reports a HIP

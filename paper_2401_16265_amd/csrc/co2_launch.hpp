@@ -56,8 +56,7 @@ struct AdamArgs {
 // wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront 4 KB
 // per buffer, an AdamW wavefront 7 KB (9 KB with the anchor).
 inline int default_sweep_waves(int delta_streams) {
-  return delta_streams <= 4 ? 8 : delta_streams <= 9 ? 7 : delta_streams <= 12 ? 6
-         : delta_streams <= 14 ? 5 : 4;
+  return delta_streams <= 4 ? 8 : delta_streams <= 9 ? 7 : 6;   // 11 and more: two load phases, see co2_sweep.hip
 }
 constexpr int kNormWavesOneBuffer = 16;
 constexpr int kNormWavesTwoBuffers = 8;

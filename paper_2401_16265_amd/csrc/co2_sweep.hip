@@ -79,12 +79,25 @@ __device__ __forceinline__ float comp(const float4& q, int e) {
   return e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
 }
 
+// With many worker buffers the tile's loads go out in two phases: the first
+// phase_a_buffers buffers together with anchor, momentum and params, the rest once
+// those have arrived (their partial sum is formed while the second phase is in
+// flight).  A wavefront then never holds more than about 11 KB of loads in
+// flight, as at K = 8, and the compute unit can keep as many wavefronts resident
+// as there; with all 3 + NB loads in flight at once it could keep only 4, too
+// few to cover each other's compute and store phases.  The order of the sum is
+// unchanged (left to right over the buffers).
+constexpr int kTwoPhaseFrom = 11;                  // fp32 buffers read; below this one phase is faster
+template <int NB, int DT>
+constexpr int phase_a_buffers() { return (DT == kDeltaF32 && NB >= kTwoPhaseFrom) ? (NB + 1) / 2 : NB; }
+
 template <int NB, bool HAS_X, int DT>
 struct SubTile {
   float4 va, vm, vx;
   typename DeltaIO<DT>::Vec vd[NB > 0 ? NB : 1];
 };
 
+// Loads of anchor, momentum, params and pseudo-gradient buffers [0, phase_a_buffers).
 template <int NB, bool HAS_X, int DT>
 __device__ __forceinline__ void load_sub(SubTile<NB, HAS_X, DT>& t, const float* x,
                                          const float* a_in, const float* m, const DeltaPtrs& d,
@@ -93,31 +106,49 @@ __device__ __forceinline__ void load_sub(SubTile<NB, HAS_X, DT>& t, const float*
   t.vm = ld4_stream(m + base, lane);
   if (HAS_X) t.vx = ld4_stream(x + base, lane);
 #pragma unroll
-  for (int k = 0; k < NB; ++k) t.vd[k] = DeltaIO<DT>::load4(d.p[k], base, lane);
+  for (int k = 0; k < phase_a_buffers<NB, DT>(); ++k) t.vd[k] = DeltaIO<DT>::load4(d.p[k], base, lane);
 }
 
 // Update and store one 256-coordinate tile held in registers.
 template <int NB, bool HAS_X, int DT>
-__device__ __forceinline__ void finish_sub(const SubTile<NB, HAS_X, DT>& t, float* x,
-                                           float* a_out, float* m, void* dout, int64_t base,
-                                           int lane, float inv, const SweepScalars& h,
+__device__ __forceinline__ void finish_sub(SubTile<NB, HAS_X, DT>& t, float* x,
+                                           float* a_out, float* m, const DeltaPtrs& d, void* dout,
+                                           int64_t base, int lane, float inv, const SweepScalars& h,
                                            const SweepMode& mode,
                                            double& acc_m, double& acc_d, int& nclip) {
   using IO = DeltaIO<DT>;
-  float mc[4], xc[4], dc[4], lc[4];
+  constexpr int NA = phase_a_buffers<NB, DT>();
+  float mc[4], xc[4], dc[4], lc[4], sum[4];
+  if constexpr (NA < NB) {
+    // second phase: wait for the first, then issue the remaining buffers' loads
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int k = NA; k < NB; ++k) t.vd[k] = IO::load4(d.p[k], base, lane);
+  }
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const float ae = comp(t.va, e);
-    float dk[NB > 0 ? NB : 1];
-#pragma unroll
-    for (int k = 0; k < NB; ++k) dk[k] = IO::get(t.vd[k], e);
     dc[e] = 0.0f;
     if (HAS_X) {
-      dc[e] = IO::stored(ae - comp(t.vx, e));
+      dc[e] = IO::stored(comp(t.va, e) - comp(t.vx, e));
       acc_d += sq(dc[e]);
     }
+    // sum over the workers, left to right; in the current-round order the worker's own
+    // pseudo-gradient formed above leads
+    if constexpr (NB == 0) {
+      sum[e] = dc[e];
+    } else {
+      const float d0 = IO::get(t.vd[0], e);
+      sum[e] = mode.own_current ? dc[e] + d0 : d0;
+#pragma unroll
+      for (int k = 1; k < NA; ++k) sum[e] = sum[e] + IO::get(t.vd[k], e);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+#pragma unroll
+    for (int k = NA; k < NB; ++k) sum[e] = sum[e] + IO::get(t.vd[k], e);
     mc[e] = comp(t.vm, e);
-    xc[e] = outer_coord(ae, mc[e], mean_of_workers<NB>(dk, dc[e], mode.own_current, h.rK), inv, h);
+    xc[e] = outer_coord(comp(t.va, e), mc[e], sum[e] * h.rK, inv, h);
     if (HAS_X) lc[e] = local_after(comp(t.vx, e), xc[e], mode.pull, mode.rho);
     acc_m += sq(clip_coord(mc[e], h.phi));
     nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));   // wavefront-uniform count
@@ -151,7 +182,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
     const float inv = inv_tab[s_lo];
     double acc_m = 0.0, acc_d = 0.0;
     int nclip = 0;
-    finish_sub<NB, HAS_X, DT>(cur, x, a_out, m, dout, base, lane, inv, h, mode, acc_m, acc_d, nclip);
+    finish_sub<NB, HAS_X, DT>(cur, x, a_out, m, d, dout, base, lane, inv, h, mode, acc_m, acc_d, nclip);
     const double tm = wave_sum(acc_m);
     double td = 0.0;
     if (HAS_X) td = wave_sum(acc_d);
@@ -343,10 +374,13 @@ __global__ __launch_bounds__(kWave) void copy_f32(const float* __restrict__ src,
 template <int NB, bool HAS_X, int DT>
 static hipError_t launch_sweep_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  // 16-bit pseudo-gradients put half the bytes per stream in flight: cap like NB/2 fp32 streams
+  // 16-bit pseudo-gradients put half the bytes per stream in flight: cap like NB/2 fp32 streams.
+  // Kernels with two load phases hold at most ~11 KB in flight per wavefront like K = 8, but run
+  // fastest with slightly fewer wavefronts (measured at 1.3B: 6 at K = 12, 5 at K = 16).
+  constexpr bool kTwoPhase = phase_a_buffers<NB, DT>() < NB;
   const int streams = DT == kDeltaF32 ? NB : (NB + 1) / 2;
-  const unsigned lds = throttle_lds_bytes(g.waves_per_cu > 0 ? g.waves_per_cu
-                                                              : default_sweep_waves(streams));
+  const int dflt = !kTwoPhase ? default_sweep_waves(streams) : NB > 12 ? 5 : 6;
+  const unsigned lds = throttle_lds_bytes(g.waves_per_cu > 0 ? g.waves_per_cu : dflt);
   const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
   hipLaunchKernelGGL((fused_sweep<NB, HAS_X, DT>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,
                      g.a_out, g.m, g.d, g.dout, g.inv, g.off_dev, g.S, g.n, h, g.mode, g.slots);

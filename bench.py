@@ -73,6 +73,8 @@ def parse():
     ap.add_argument("--side-waves", type=int, default=-1,
                     help="350m_overlap only: sweep_waves_per_cu of the side-stream outer update "
                          "(-1 = the schedule's default)")
+    ap.add_argument("--plain-buffers", action="store_true",
+                    help="350m_overlap only: separate plain allocations instead of one buffer set")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -191,13 +193,20 @@ def overlap_bench(args):
     hp = {k: v for k, v in cfg.adamw.items() if k != "grad_std"}
     init = co2_inputs.fill_normal_(torch.empty(n, dtype=torch.float32, device=dev), cfg.param_std,
                                    co2_inputs.seed_for(cfg.seed, 1))
-    grads = [co2_inputs.fill_bf16_normal_(torch.empty(n, dtype=torch.bfloat16, device=dev),
-                                          cfg.adamw["grad_std"], co2_inputs.seed_for(cfg.seed, 10 + k))
-             for k in range(tau)]
+    use_set = not args.plain_buffers
+
+    def make_grads(w):
+        """tau bf16 gradient buffers: in the worker's buffer set when it has one."""
+        bufs = ([v.view(torch.bfloat16) for v in w.extra] if use_set else
+                [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)])
+        return [co2_inputs.fill_bf16_normal_(g, cfg.adamw["grad_std"], co2_inputs.seed_for(cfg.seed, 10 + k))
+                for k, g in enumerate(bufs)]
     rounds = max(args.steps, 12)
     res = {}
     for mode in ("serial", "overlapped"):
-        w = CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**hp), dev, init)
+        w = CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**hp), dev, init,
+                      buffer_set=use_set, extra_bytes=[2 * n] * tau if use_set else ())
+        grads = make_grads(w)
         if args.side_waves >= 0:
             w.side_waves = args.side_waves
         for j, pb in enumerate(w.peers):
@@ -215,6 +224,9 @@ def overlap_bench(args):
         res[mode] = {"median_ms": statistics.median(per[10:]), "min_ms": min(per[10:]),
                      "wall_ms_per_round": wall * 1e3 / rounds}
         w_side_waves = w.side_waves
+        del grads
+        torch.cuda.synchronize()
+        w.close()
         del w
         torch.cuda.empty_cache()
     bytes_round = (26 * tau + 8 + 4) * n + (16 + 4 * K) * n   # AdamW steps (+dout, +anchor read) + split outer update
@@ -224,6 +236,7 @@ def overlap_bench(args):
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{cfg.name}: n={n}, K={K}, tau={tau}, bf16 grads, fp32 master",
                       "side_stream_sweep_waves_per_cu": w_side_waves,
+                      "buffers": "one buffer set (64 MiB pieces)" if use_set else "separate plain allocations",
                       "compacted_gib": round(compacted / 2**30, 1)},
            "serial": res["serial"], "overlapped": res["overlapped"],
            "overlap_speedup": res["serial"]["median_ms"] / res["overlapped"]["median_ms"],

@@ -57,20 +57,40 @@ class CO2Worker:
 
     def __init__(self, table: co2.SegmentTable, K: int, tau: int, alpha: float, beta: float,
                  clip_phi: float, penalty_c: float, adamw: AdamWConfig, device,
-                 params_init: torch.Tensor):
+                 params_init: torch.Tensor, buffer_set: bool = False, extra_bytes=()):
+        """buffer_set: take all flat buffers from ONE co2.BufferSet (the layout the sweep and
+        the AdamW step run fastest on) instead of separate allocations; `extra_bytes` then
+        asks for further buffers in the same set for the caller (e.g. its gradient buffers),
+        handed back as uint8 views in `self.extra`."""
         self.table, self.K, self.tau = table, K, tau
         self.alpha, self.beta, self.phi, self.c = alpha, beta, clip_phi, penalty_c
         self.hp = adamw
         n, S = table.n, table.S
         self.n, self.S = n, S
         f32 = dict(dtype=torch.float32, device=device)
-        self.params = params_init.clone()
-        self.exp_avg = torch.zeros(n, **f32)
-        self.exp_avg_sq = torch.zeros(n, **f32)
-        self.anchor = [params_init.clone(), torch.empty(n, **f32)]
-        self.momentum = torch.zeros(n, **f32)                      # m_0 = 0
-        self.own = [torch.zeros(n, **f32), torch.zeros(n, **f32)]
-        self.peers = [torch.zeros(n, **f32) for _ in range(K - 1)]
+        self.extra, self._set = [], None
+        if buffer_set:
+            count = 8 + (K - 1)
+            self._set = co2.BufferSet([4 * n] * count + [int(b) for b in extra_bytes], 0, device)
+            flat = [v.view(torch.float32) for v in self._set.views[:count]]
+            self.extra = list(self._set.views[count:])
+            for t in flat[1:3] + flat[5:]:
+                t.zero_()
+            self.params, self.exp_avg, self.exp_avg_sq = flat[0], flat[1], flat[2]
+            self.anchor = [flat[3], flat[4]]
+            self.momentum = flat[5]                                # m_0 = 0
+            self.own = [flat[6], flat[7]]
+            self.peers = flat[8:]
+            self.params.copy_(params_init)
+            self.anchor[0].copy_(params_init)
+        else:
+            self.params = params_init.clone()
+            self.exp_avg = torch.zeros(n, **f32)
+            self.exp_avg_sq = torch.zeros(n, **f32)
+            self.anchor = [params_init.clone(), torch.empty(n, **f32)]
+            self.momentum = torch.zeros(n, **f32)                      # m_0 = 0
+            self.own = [torch.zeros(n, **f32), torch.zeros(n, **f32)]
+            self.peers = [torch.zeros(n, **f32) for _ in range(K - 1)]
         self.step_sq = [torch.zeros(S, dtype=torch.float64, device=device) for _ in range(2)]
         self.fsn = [torch.zeros(S, **f32) for _ in range(2)]
         self.lam = torch.ones(S, **f32)
@@ -86,6 +106,14 @@ class CO2Worker:
         # Resident-wavefront cap of the side-stream sweep while it shares the GPU with
         # the AdamW steps (co2_params.sweep_waves_per_cu; 0 = the sweep's stand-alone default)
         self.side_waves = 0
+
+    def close(self):
+        """Frees a buffer set taken at construction (all work on the buffers has completed)."""
+        if self._set is not None:
+            for name in ("params", "exp_avg", "exp_avg_sq", "anchor", "momentum", "own", "peers", "extra"):
+                setattr(self, name, None)
+            self._set.close()
+            self._set = None
 
     # ------------------------------------------------------------------ pieces
     def _inner_loop(self, grads: List[torch.Tensor], stream):

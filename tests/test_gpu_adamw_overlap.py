@@ -128,13 +128,14 @@ class OracleWorker:
         self.t += 1
 
 
-def run_rounds(dev, table, sample, K, tau, rounds, seed, phi):
+def run_rounds(dev, table, sample, K, tau, rounds, seed, phi, buffer_set=False):
     seg = co2.SegmentTable(table, dev)
     n = seg.n
     f32 = dict(dtype=torch.float32, device=dev)
     init = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(seed, 1))
-    mk = lambda: CO2Worker(seg, K, tau, 1.0, 0.9, phi, 1.0, AdamWConfig(**HP), dev, init)  # noqa: E731
-    w_ov, w_se = mk(), mk()
+    mk = lambda bs: CO2Worker(seg, K, tau, 1.0, 0.9, phi, 1.0, AdamWConfig(**HP), dev, init,  # noqa: E731
+                              buffer_set=bs)
+    w_ov, w_se = mk(buffer_set), mk(False)
     ow = OracleWorker(table, sample, K, tau, 1.0, 0.9, phi, 1.0, init)
     grads = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)]
     for t in range(rounds):
@@ -171,6 +172,15 @@ def test_overlapped_rounds_small(dev):
     w, ow = run_rounds(dev, table, list(range(len(table) - 1)), K=4, tau=3, rounds=6, seed=4,
                        phi=1e-3)
     assert np.all(ow.lam >= 1.0) and np.any(ow.lam > 1.0)
+
+
+def test_overlapped_rounds_in_a_buffer_set(dev):
+    """The worker's flat buffers taken from one co2_buffer_set (piece-major layout):
+    same bits as with separate allocations, and the oracle's."""
+    table = co2_inputs.gpt_table(layers=2, d=65, ffn=257, vocab=1001, ctx=33)
+    w, ow = run_rounds(dev, table, list(range(len(table) - 1)), K=4, tau=3, rounds=4, seed=8,
+                       phi=1e-3, buffer_set=True)
+    w.close()
 
 
 def test_overlapped_rounds_tau_one(dev):

@@ -39,8 +39,8 @@ import torch
 PAGE = 4096
 DEFAULT_GAPS = (PAGE, 11 * PAGE, 259 * PAGE)    # odd page counts; 0, 2 pages and 1 MiB measure 1-3 % slower
 # Piece size of the piece-major buffer sets.  Measured at 1.3B parameters (fp32 buffers of 5.4 GB): sets with
-# 64 MiB pieces were fast every time (three sets held together, several processes, K = 8, 12, 16), 32 MiB
-# nearly as good, 128 MiB consistently 5 % slower, 256 MiB - 2 GiB anything in between.
+# 64 MiB pieces were fast every time (three sets held together, several processes, K = 8, 12, 16), as were
+# 48-70 MiB; 16 MiB and 128 MiB were consistently 4-5 % slower, 256 MiB - 2 GiB anything in between.
 DEFAULT_PIECES = (64 << 20,)
 
 

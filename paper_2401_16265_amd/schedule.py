@@ -25,7 +25,7 @@ the kernels of libco2.
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Optional
+from typing import List
 
 import torch
 

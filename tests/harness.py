@@ -12,7 +12,7 @@ host; nothing the HIP library computes is ever fed to the oracle.
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Optional, Sequence
+from typing import Optional, Sequence
 
 import numpy as np
 import torch

@@ -205,7 +205,11 @@ class StreamedOuterStepHarness:
                  sample: Optional[Sequence[int]] = None, drift: str = "normal",
                  drift_scale: float = 1e-3, drift_nu: int = 3, param_std: float = 0.02,
                  momentum_std: float = 0.02, start_step: int = 1, bf16: bool = False,
-                 transport: Optional[str] = None, chunk_elems: int = 1 << 26, workers: int = 8):
+                 transport: Optional[str] = None, chunk_elems: int = 1 << 26, workers: int = 8,
+                 nonstale: bool = False, norm_clip: bool = False, pull_rho: float = 1.0,
+                 use_first_step_norm: bool = False):
+        self.nonstale, self.norm_clip, self.pull_rho = nonstale, norm_clip, pull_rho
+        self.variant = nonstale or norm_clip or pull_rho != 1.0
         self.table = [int(o) for o in table]
         self.n, self.S = self.table[-1], len(self.table) - 1
         self.transport = transport or ("bf16" if bf16 else "f32")
@@ -233,7 +237,9 @@ class StreamedOuterStepHarness:
             co2_inputs.fill_normal_(self.m, momentum_std, co2_inputs.seed_for(seed, 2))
         else:
             self.m.zero_()
-        self.t = start_step
+        self.t = self.t0 = start_step
+        self.fsn = torch.empty(self.S, **f32) if use_first_step_norm else None
+        assert not (self.variant and bf16)
         # staging: the K-1 peers + the drift as inputs; outputs reuse the same arrays afterwards
         self.sets = staging_sets(workers, max(K, 4), 4 * self.ch.max_chunk)
         # ---- oracle state over the compact index space
@@ -241,7 +247,8 @@ class StreamedOuterStepHarness:
         self.o_a = np.empty(nc, dtype=np.float32)
         self.o_m = np.empty(nc, dtype=np.float32)
         self.o_own = np.zeros(nc, dtype=np.uint16 if bf16 else np.float32)
-        if start_step >= 1:
+        self.o_x = np.empty(nc, dtype=np.float32) if pull_rho != 1.0 else None   # pulled local parameters
+        if start_step >= 1 and not nonstale:
             # no earlier round produced the worker's own previous pseudo-gradient: drawn like a peer's
             self._fill_drift(self.own[start_step % 2], 99)
         ready = torch.cuda.Event()
@@ -252,7 +259,7 @@ class StreamedOuterStepHarness:
             try:
                 self.o_a[c.c0:c.c1] = stage(self.a, c, st[0], ready)
                 self.o_m[c.c0:c.c1] = stage(self.m, c, st[1], ready)
-                if start_step >= 1:
+                if start_step >= 1 and not nonstale:
                     self.o_own[c.c0:c.c1] = stage(self.own[start_step % 2], c, st[2], ready)
             finally:
                 self.sets.put(st)
@@ -273,16 +280,29 @@ class StreamedOuterStepHarness:
         dict(bit_exact, worst, nclipped, lam_min, lam_max)."""
         hp, t, K = self.hp, self.t, self.hp.K
         cur, nxt = self.own[t % 2], self.own[(t + 1) % 2]       # cur: deltas[0]; nxt: delta_out
-        if t >= 1:
+        if t >= 1 or self.nonstale:
             for k, pbuf in enumerate(self.peers):               # before the drift: bf16 peers are drawn through `noise`
                 self._fill_drift(pbuf, 200 + k)
         self._fill_drift(self.noise, 100)
-        torch.add(self.a, self.noise, out=self.x)               # inner loop stand-in
+        pulled = self.pull_rho != 1.0 and t > self.t0           # local parameters carried over, not restarted
+        torch.add(self.x if pulled else self.a, self.noise, out=self.x)   # inner loop stand-in
+        o_fsn = None
+        if self.fsn is not None:
+            co2_inputs.fill_normal_(self.fsn, 1.0, co2_inputs.seed_for(self.seed, 300, t))
+            self.fsn.abs_().mul_(self.drift_scale * 10).add_(self.drift_scale)
+            o_fsn = self.fsn[self.ch.sample].cpu().numpy().copy()
+        if self.nonstale:
+            flags |= co2.CO2_FLAG_CURRENT_ROUND
+        if self.norm_clip:
+            flags |= co2.CO2_FLAG_NORM_CLIP
+        if self.pull_rho != 1.0:
+            flags |= co2.CO2_FLAG_ANCHOR_PULL
         p = co2.make_params(self.seg, K, hp.alpha, hp.beta, hp.phi, hp.c, hp.tau, t, flags,
-                            clipped_out=self.clipped)
+                            clipped_out=None if self.norm_clip else self.clipped, pull_rho=self.pull_rho)
         entry = {"f32": co2.co2_outer_step, "bf16": co2.co2_outer_step_bf16,
                  "f16": co2.co2_outer_step_f16}[self.transport]
-        entry(p, self.x, self.a, self.a, self.m, [cur] + self.peers, nxt, None, self.lam, self.ws)
+        entry(p, self.x, self.a, self.a, self.m, [None if self.nonstale else cur] + self.peers, nxt,
+              self.fsn, self.lam, self.ws)
         ready = torch.cuda.Event()
         ready.record()
         params_equal_anchor = torch.equal(self.x, self.a)       # both hold x_{t+1,0}
@@ -290,6 +310,7 @@ class StreamedOuterStepHarness:
         S_c = len(self.ch.sample)
         o_lam = np.ones(S_c, dtype=np.float32)
         o_clip = np.zeros(S_c, dtype=np.int64)
+        o_scale = np.ones(S_c, dtype=np.float32)
         stats = {"bit_exact": True, "worst": 0.0}
         lock = threading.Lock()
         oracle_step = {"f32": co2_oracle.outer_step_f32, "bf16": co2_oracle.outer_step_bf16,
@@ -300,16 +321,29 @@ class StreamedOuterStepHarness:
             st = self.sets.get()
             try:
                 sl = slice(c.c0, c.c1)
-                o_x = self.o_a[sl] + stage(self.noise, c, st[0], ready)     # same fp32 add as on the device
+                start = self.o_x[sl] if pulled else self.o_a[sl]
+                o_x = start + stage(self.noise, c, st[0], ready)             # same fp32 add as on the device
                 o_d = None
-                if t >= 1:
+                if t >= 1 or self.nonstale:
                     o_d = [self.o_own[sl]] + [stage(pb, c, st[1 + k], ready)
                                               for k, pb in enumerate(self.peers)]
-                out = oracle_step(seg_off=c.table, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c,
-                                  tau=hp.tau, step=t, x=o_x, a=self.o_a[sl], m=self.o_m[sl], deltas=o_d)
+                kw = dict(seg_off=c.table, alpha=hp.alpha, beta=hp.beta, phi=hp.phi, c=hp.c, tau=hp.tau,
+                          step=t, x=o_x, a=self.o_a[sl], m=self.o_m[sl], deltas=o_d,
+                          first_step_norm=None if o_fsn is None else o_fsn[c.i0:c.i1])
+                if self.variant:
+                    if self.nonstale:
+                        o_d[0] = np.full(c.elems, 1e3, np.float32)           # poison: must not be read
+                    out = co2_oracle.outer_step_variant_f32(nonstale=self.nonstale, norm_clip=self.norm_clip,
+                                                            pull_rho=self.pull_rho, **kw)
+                else:
+                    out = oracle_step(**kw)
                 self.o_own[sl] = out["dout"]
                 local = {"bit_exact": True, "worst": 0.0}
-                assert np.array_equal(o_x, self.o_a[sl]), "oracle: params and anchor must both hold x_{t+1,0}"
+                if self.o_x is not None:
+                    self.o_x[sl] = o_x
+                    same_or_close(stage(self.x, c, st[3], ready), o_x, "params", local)
+                else:
+                    assert np.array_equal(o_x, self.o_a[sl]), "oracle: params and anchor must both hold x_{t+1,0}"
                 same_or_close(stage(self.a, c, st[0], ready), self.o_a[sl], "anchor", local)
                 same_or_close(stage(self.m, c, st[1], ready), self.o_m[sl], "momentum", local)
                 g_d = stage(nxt, c, st[2], ready)
@@ -317,8 +351,10 @@ class StreamedOuterStepHarness:
                     assert np.array_equal(g_d, out["dout"]), "delta_out (16-bit patterns) differs"
                 else:
                     same_or_close(g_d, out["dout"], "delta_out", local)
+                if self.variant:
+                    o_scale[c.i0:c.i1] = out["scale"]
                 o_lam[c.i0:c.i1] = out["lam"]
-                if t >= 1:
+                if (t >= 1 or self.nonstale) and not self.norm_clip:
                     om = self.o_m[sl]
                     for i in range(c.i0, c.i1):
                         lo, hi = int(c.table[i - c.i0]), int(c.table[i - c.i0 + 1])
@@ -332,10 +368,14 @@ class StreamedOuterStepHarness:
 
         for_each_chunk(self.ch, work, self.workers)
         torch.cuda.synchronize()
-        assert params_equal_anchor, "device: params and anchor must both hold x_{t+1,0}"
-        g_clip = self.clipped[self.ch.sample].cpu().numpy()
-        assert np.array_equal(g_clip, o_clip), "clipped-coordinate counts differ"
-        if t >= 1:
+        if self.pull_rho == 1.0:
+            assert params_equal_anchor, "device: params and anchor must both hold x_{t+1,0}"
+        if not self.norm_clip:
+            g_clip = self.clipped[self.ch.sample].cpu().numpy()
+            assert np.array_equal(g_clip, o_clip), "clipped-coordinate counts differ"
+        else:
+            stats["rescaled_segments"] = int(np.count_nonzero(o_scale < 1.0))
+        if t >= 1 or self.nonstale:
             g_lam = self.lam[self.ch.sample].cpu().numpy()
             e = rel_err(g_lam, o_lam)
             assert e <= REL_TOL, f"Lambda: max relative error {e:.3e}"

@@ -184,3 +184,38 @@ def test_f16_deltas_7b_shard_every_element(dev):
         res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 2 else 0)
         print(f"  7b shard f16 step {h.t - 1}: {res}", flush=True)
     assert res["lam_max"] > 1.0
+
+
+def test_variants_7b_shard_every_element(dev):
+    """All three switches together on one 7B shard at its real size (421M parameters,
+    K=8, partial first/last tensors): every element of params, anchor, momentum and
+    delta_out and every Lambda against the oracle's own full state, four rounds from
+    round 0, carried sums from the second; the pulled local parameters carry over."""
+    cfg = co2_inputs.CONFIGS["7b_shard"]
+    table = co2_inputs.config_table(cfg, rank=1)
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=0.5, c=cfg.c, tau=cfg.tau)
+    h = StreamedOuterStepHarness(table, hp, dev, seed=61, drift_scale=cfg.drift_scale,
+                                 momentum_std=cfg.momentum_std, start_step=0, chunk_elems=1 << 25,
+                                 nonstale=True, norm_clip=True, pull_rho=0.5, use_first_step_norm=True)
+    assert h.ch.n == 421_150_976
+    rescaled = []
+    for i in range(4):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 1 else 0)
+        print(f"  7b shard variants round {h.t - 1}: {res}", flush=True)
+        rescaled.append(res["rescaled_segments"])
+    assert res["lam_max"] > 1.0
+    assert 0 < max(rescaled) < len(table) - 1, "the rescale should bite on some segments only"
+
+
+@pytest.mark.parametrize("variant", ["anchor_pull", "norm_clip"])
+def test_single_variant_gpt2_small_every_element(dev, variant):
+    """One switch at a time on the GPT-2-small table, stale order, every element, 3 rounds."""
+    cfg = co2_inputs.CONFIGS["gpt2s"]
+    table = co2_inputs.config_table(cfg)
+    hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=0.05, c=cfg.c, tau=cfg.tau)
+    h = StreamedOuterStepHarness(table, hp, dev, seed=62, drift_scale=cfg.drift_scale,
+                                 momentum_std=1e-3, start_step=1, chunk_elems=1 << 24, **VARIANTS[variant])
+    for i in range(3):
+        res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 1 else 0)
+        print(f"  gpt2s {variant} round {h.t - 1}: {res}", flush=True)
+    assert res["lam_max"] > 1.0

@@ -3,7 +3,10 @@
 // called directly, results compared element by element with the CPU oracle
 // (linked in from oracle/co2_oracle.cpp -- this program is a test).
 //
-//   co2_selftest [n] [K] [buffer_set]   exit code 0 = every element within 1e-5 relative
+//   co2_selftest [n] [K] [buffer_set] [mode]   exit code 0 = every element within 1e-5 relative
+//   mode 0: co2_outer_step;  1: co2_outer_step_static (no workspace argument);
+//        2: co2_outer_step with all three variant switches (current-round mean, anchor pull,
+//           clipping by norm rescale) against the oracle's variant function
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -21,6 +24,13 @@ extern "C" int co2_oracle_outer_step_f32(int64_t n, int32_t S, const int64_t* se
                                          float* m, const float* const* d, float* dout,
                                          const float* first_step_norm, float* lambda_out,
                                          double* M2_out, double* T_out, int64_t* nclipped);
+extern "C" int co2_oracle_outer_step_variant_f32(int64_t n, int32_t S, const int64_t* seg_off, int32_t K,
+                                                 float alpha, float beta, float phi, float c, int32_t tau,
+                                                 int64_t step, int32_t nonstale, int32_t norm_clip,
+                                                 float pull_rho, float* x, const float* a_in, float* a_out,
+                                                 float* m, const float* const* d, float* dout,
+                                                 const float* first_step_norm, float* lambda_out,
+                                                 float* scale_out, int64_t* nclipped);
 
 #define HIP_OK(call)                                                                      \
   do {                                                                                    \
@@ -55,11 +65,15 @@ int main(int argc, char** argv) {
   const int64_t n = argc > 1 ? std::atoll(argv[1]) : 100003;
   const int32_t K = argc > 2 ? std::atoi(argv[2]) : 3;
   const bool use_set = argc > 3 && std::atoi(argv[3]) != 0;   // buffers from co2_buffer_set_create
-  if (n < 8 || K < 1 || K > CO2_MAX_K) { std::fprintf(stderr, "bad arguments\n"); return 2; }
+  const int mode = argc > 4 ? std::atoi(argv[4]) : 0;
+  const bool variant = mode == 2;
+  if (n < 8 || K < 1 || K > CO2_MAX_K || mode < 0 || mode > 2) { std::fprintf(stderr, "bad arguments\n"); return 2; }
   const std::vector<int64_t> seg = {0, 5, 5, n / 3 + 1, n - 2, n};
   const int32_t S = static_cast<int32_t>(seg.size()) - 1;
-  const float alpha = 0.9f, beta = 0.9f, phi = 2e-3f, c = 1.0f;
+  const float alpha = 0.9f, beta = 0.9f, phi = variant ? 2e-2f : 2e-3f, c = 1.0f, rho = 0.5f;
   const int32_t tau = 4;
+  std::vector<float> fsn(S);
+  for (int32_t s = 0; s < S; ++s) fsn[s] = 1e-3f * (1.0f + 0.25f * static_cast<float>(s));
 
   std::vector<float> a(n), x(n), m(n, 0.0f), dout(n), lam(S);
   std::vector<std::vector<float>> d(K, std::vector<float>(n, 0.0f));
@@ -90,6 +104,9 @@ int main(int argc, char** argv) {
     HIP_OK(hipMalloc(&ddout[0], nb)); HIP_OK(hipMalloc(&ddout[1], nb));
     for (int k = 1; k < K; ++k) HIP_OK(hipMalloc(&dd[k], nb));
   }
+  float* dfsn;
+  HIP_OK(hipMalloc(&dfsn, sizeof(float) * S));
+  HIP_OK(hipMemcpy(dfsn, fsn.data(), sizeof(float) * S, hipMemcpyHostToDevice));
   HIP_OK(hipMalloc(&dlam, sizeof(float) * S)); HIP_OK(hipMalloc(&dseg, sizeof(int64_t) * (S + 1)));
   HIP_OK(hipMalloc(&ws, wsb));
   HIP_OK(hipMemcpy(da, a.data(), nb, hipMemcpyHostToDevice));
@@ -100,7 +117,9 @@ int main(int argc, char** argv) {
   std::vector<float> got(n);
   for (int64_t t = 0; t < 4; ++t) {
     // inner loop stand-in: local params drift from the anchor; peers' deltas arrive
-    for (int64_t j = 0; j < n; ++j) x[j] = a[j] + 1e-3f * unit((uint64_t(t + 1) << 40) + j);
+    // (with the anchor pull the local parameters carry over instead of restarting from the anchor)
+    for (int64_t j = 0; j < n; ++j)
+      x[j] = ((variant && t > 0) ? x[j] : a[j]) + 1e-3f * unit((uint64_t(t + 1) << 40) + j);
     for (int k = 1; k < K; ++k)
       for (int64_t j = 0; j < n; ++j) d[k][j] = 1e-3f * unit((uint64_t(100 + k) << 48) + (uint64_t(t) << 40) + j);
     HIP_OK(hipMemcpy(dx, x.data(), nb, hipMemcpyHostToDevice));
@@ -111,16 +130,32 @@ int main(int argc, char** argv) {
     p.n = n; p.S = S; p.K = K; p.seg_off = seg.data(); p.seg_off_dev = dseg;
     p.alpha = alpha; p.beta = beta; p.clip_phi = phi; p.penalty_c = c; p.tau = tau;
     p.flags = t >= 2 ? CO2_FLAG_CARRIED_NORMS : CO2_FLAG_NONE; p.step = t;
-    const int rc = co2_outer_step(&p, dx, da, da, dm, dd.data(), ddout[t % 2], nullptr, dlam, ws, wsb, nullptr);
+    int rc;
+    if (mode == 1) {
+      rc = co2_outer_step_static(&p, dx, da, da, dm, dd.data(), ddout[t % 2], nullptr, dlam, nullptr);
+    } else if (variant) {
+      p.flags = (t >= 1 ? CO2_FLAG_CARRIED_NORMS : CO2_FLAG_NONE) | CO2_FLAG_CURRENT_ROUND |
+                CO2_FLAG_ANCHOR_PULL | CO2_FLAG_NORM_CLIP;
+      p.pull_rho = rho;
+      dd[0] = nullptr;                          // not read in the current-round order
+      rc = co2_outer_step(&p, dx, da, da, dm, dd.data(), ddout[t % 2], dfsn, dlam, ws, wsb, nullptr);
+    } else {
+      rc = co2_outer_step(&p, dx, da, da, dm, dd.data(), ddout[t % 2], nullptr, dlam, ws, wsb, nullptr);
+    }
     if (rc != CO2_OK) { std::fprintf(stderr, "co2_outer_step: %s\n", co2_strerror(rc)); return 1; }
     HIP_OK(hipDeviceSynchronize());
 
     // the oracle carries its own state: a, x, m, d[0] (its own previous delta_out)
     std::vector<const float*> dp(K);
     for (int k = 0; k < K; ++k) dp[k] = d[k].data();
-    if (co2_oracle_outer_step_f32(n, S, seg.data(), K, alpha, beta, phi, c, tau, t, x.data(), a.data(),
-                                  a.data(), m.data(), t ? dp.data() : nullptr, dout.data(), nullptr,
-                                  lam.data(), nullptr, nullptr, nullptr) != 0) {
+    const int orc = variant
+        ? co2_oracle_outer_step_variant_f32(n, S, seg.data(), K, alpha, beta, phi, c, tau, t, 1, 1, rho,
+                                            x.data(), a.data(), a.data(), m.data(), dp.data(), dout.data(),
+                                            fsn.data(), lam.data(), nullptr, nullptr)
+        : co2_oracle_outer_step_f32(n, S, seg.data(), K, alpha, beta, phi, c, tau, t, x.data(), a.data(),
+                                    a.data(), m.data(), t ? dp.data() : nullptr, dout.data(), nullptr,
+                                    lam.data(), nullptr, nullptr, nullptr);
+    if (orc != 0) {
       std::fprintf(stderr, "oracle rejected its arguments\n");
       return 1;
     }
@@ -129,7 +164,7 @@ int main(int argc, char** argv) {
     HIP_OK(hipMemcpy(got.data(), da, nb, hipMemcpyDeviceToHost)); ok = ok && close(got, a, "anchor");
     HIP_OK(hipMemcpy(got.data(), dm, nb, hipMemcpyDeviceToHost)); ok = ok && close(got, m, "momentum");
     HIP_OK(hipMemcpy(got.data(), ddout[t % 2], nb, hipMemcpyDeviceToHost)); ok = ok && close(got, dout, "delta_out");
-    if (t >= 1) {
+    if (t >= 1 || variant) {
       std::vector<float> glam(S);
       HIP_OK(hipMemcpy(glam.data(), dlam, sizeof(float) * S, hipMemcpyDeviceToHost));
       ok = ok && close(glam, lam, "Lambda");
@@ -146,6 +181,8 @@ int main(int argc, char** argv) {
     HIP_OK(hipDeviceSynchronize());
     if (co2_buffer_set_destroy(set) != CO2_OK) { std::fprintf(stderr, "co2_buffer_set_destroy failed\n"); return 1; }
   }
-  std::printf("PASS n=%lld K=%d buffers=%s\n", static_cast<long long>(n), K, use_set ? "buffer set" : "hipMalloc");
+  std::printf("PASS n=%lld K=%d buffers=%s entry=%s\n", static_cast<long long>(n), K,
+              use_set ? "buffer set" : "hipMalloc",
+              mode == 1 ? "co2_outer_step_static" : variant ? "co2_outer_step, variant switches" : "co2_outer_step");
   return 0;
 }

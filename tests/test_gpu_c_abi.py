@@ -1,6 +1,7 @@
 """The C ABI driven without PyTorch: a host-only C++ program (tests/c_abi/selftest.cpp)
-allocates with hipMalloc (or co2_buffer_set_create), calls libco2.so directly for four consecutive rounds and
-compares every element with the oracle source linked into it."""
+allocates with hipMalloc (or co2_buffer_set_create), calls libco2.so directly for four consecutive rounds --
+through co2_outer_step, co2_outer_step_static or co2_outer_step with the variant switches -- and compares every
+element with the oracle source linked into it."""
 import importlib.util
 import os
 import subprocess
@@ -18,8 +19,13 @@ def _exe():
     return mod.EXE if os.path.exists(mod.EXE) else mod.build_selftest()
 
 
-@pytest.mark.parametrize("n,K,buffer_set", [(100003, 3, 0), (4099, 16, 0), (1 << 20, 8, 0), (1 << 20, 8, 1)])
-def test_c_abi_selftest(n, K, buffer_set):
-    out = subprocess.run([_exe(), str(n), str(K), str(buffer_set)], capture_output=True, text=True, timeout=120)
+@pytest.mark.parametrize("n,K,buffer_set,mode", [
+    (100003, 3, 0, 0), (4099, 16, 0, 0), (1 << 20, 8, 0, 0), (1 << 20, 8, 1, 0),
+    (100003, 3, 0, 1), (1 << 20, 8, 1, 1),          # the entry point that allocates nothing
+    (100003, 3, 0, 2), (4099, 1, 0, 2), (1 << 20, 8, 1, 2),   # all three variant switches
+])
+def test_c_abi_selftest(n, K, buffer_set, mode):
+    out = subprocess.run([_exe(), str(n), str(K), str(buffer_set), str(mode)], capture_output=True, text=True,
+                         timeout=120)
     print(out.stdout, out.stderr, flush=True)
     assert out.returncode == 0 and "PASS" in out.stdout

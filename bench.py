@@ -73,6 +73,10 @@ def parse():
     ap.add_argument("--side-waves", type=int, default=-1,
                     help="350m_overlap only: sweep_waves_per_cu of the side-stream outer update "
                          "(-1 = the schedule's default)")
+    ap.add_argument("--inner-gemm-tflop", type=float, default=0.0,
+                    help="350m_overlap only: run about this many TFLOP of bf16 GEMMs before each local step "
+                         "as a compute-bound stand-in for the forward/backward pass (0 = none: the round is "
+                         "then HBM-bound on both streams)")
     ap.add_argument("--plain-buffers", action="store_true",
                     help="350m_overlap only: separate plain allocations instead of one buffer set")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -203,12 +207,28 @@ def overlap_bench(args):
                 for k, g in enumerate(bufs)]
     rounds = max(args.steps, 12)
     res = {}
+    # Optional compute-bound stand-in for the forward/backward pass of each local step: a chain of
+    # bf16 GEMMs (library calls, only a load generator here) of about --inner-gemm-tflop TFLOP.
+    gemm = None
+    if args.inner_gemm_tflop > 0:
+        G = 8192
+        ga, gb, gc = (torch.randn(G, G, dtype=torch.bfloat16, device=dev) * 0.01 for _ in range(3))
+        reps = max(1, round(args.inner_gemm_tflop * 1e12 / (2 * G ** 3)))
+
+        def gemm(_k):
+            for _ in range(reps):
+                torch.matmul(ga, gb, out=gc)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        gemm(0); torch.cuda.synchronize()
+        e0.record(); gemm(0); e1.record(); torch.cuda.synchronize()
+        gemm_ms = e0.elapsed_time(e1)
     for mode in ("serial", "overlapped"):
         w = CO2Worker(seg, K, tau, cfg.alpha, cfg.beta, cfg.phi, cfg.c, AdamWConfig(**hp), dev, init,
                       buffer_set=use_set, extra_bytes=[2 * n] * tau if use_set else ())
         grads = make_grads(w)
         if args.side_waves >= 0:
             w.side_waves = args.side_waves
+        w.inner_compute = gemm
         for j, pb in enumerate(w.peers):
             co2_inputs.fill_normal_(pb, cfg.drift_scale, co2_inputs.seed_for(cfg.seed, 200 + j))
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 1)]
@@ -241,6 +261,11 @@ def overlap_bench(args):
            "serial": res["serial"], "overlapped": res["overlapped"],
            "overlap_speedup": res["serial"]["median_ms"] / res["overlapped"]["median_ms"],
            "round_gbps_algorithmic": bytes_round / (res["overlapped"]["median_ms"] * 1e-3) / 1e9}
+    if gemm is not None:
+        out["config"]["inner_compute"] = {
+            "kind": f"{reps} bf16 GEMM(s) {G}x{G}x{G} before each local step (stand-in for forward/backward)",
+            "tflop_per_local_step": reps * 2 * G ** 3 / 1e12, "ms_per_local_step_alone": gemm_ms}
+        del out["round_gbps_algorithmic"]          # the round is no longer HBM-bound
     print(json.dumps(out))
 
 

@@ -106,6 +106,9 @@ class CO2Worker:
         # Resident-wavefront cap of the side-stream sweep while it shares the GPU with
         # the AdamW steps (co2_params.sweep_waves_per_cu; 0 = the sweep's stand-alone default)
         self.side_waves = 0
+        # Optional stand-in for what produces the gradient of a local step (forward and
+        # backward pass): called as inner_compute(k) before local step k, on the main stream.
+        self.inner_compute = None
 
     def close(self):
         """Frees a buffer set taken at construction (all work on the buffers has completed)."""
@@ -123,6 +126,8 @@ class CO2Worker:
         for k in range(self.tau):
             self.adam_k += 1
             first, last = k == 0, k == self.tau - 1
+            if self.inner_compute is not None:
+                self.inner_compute(k)
             co2.co2_inner_adamw(
                 self.n, a_cur if first else self.params, self.params, grads[k], self.exp_avg,
                 self.exp_avg_sq, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, self.adam_k,

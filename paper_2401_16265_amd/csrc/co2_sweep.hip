@@ -150,7 +150,9 @@ __device__ __forceinline__ void finish_sub(SubTile<NB, HAS_X, DT>& t, float* x,
     mc[e] = comp(t.vm, e);
     xc[e] = outer_coord(comp(t.va, e), mc[e], sum[e] * h.rK, inv, h);
     if (HAS_X) lc[e] = local_after(comp(t.vx, e), xc[e], mode.pull, mode.rho);
-    acc_m += sq(clip_coord(mc[e], h.phi));
+    // the term carried to the next round's gap: Clip(m', phi)^2, or under norm rescale m'^2
+    // itself (a clamp at phi = inf would turn a NaN into inf)
+    acc_m += sq(mode.defer_iterate ? mc[e] : clip_coord(mc[e], h.phi));
     nclip += __popcll(__ballot(fabsf(mc[e]) > h.phi));   // wavefront-uniform count
   }
   constexpr int kTileBytes = kWave * 16;
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(kWave) void fused_sweep(
         dj = IO::stored(a - xj);
       }
       const float xn = outer_coord(a, mj, mean_of_workers<NB>(dk, dj, mode.own_current, h.rK), inv, h);
-      acc_m += sq(clip_coord(mj, h.phi));
+      acc_m += sq(mode.defer_iterate ? mj : clip_coord(mj, h.phi));
       if (fabsf(mj) > h.phi) acc_c += 1.0;
       if (HAS_X) {
         acc_d += sq(dj);

@@ -290,7 +290,10 @@ int co2_pseudo_grad_norms(const co2_params* p, const float* const* bufs, int32_t
  *   p' = p_in*(1 - lr*wd) - (float)(lr/(1-beta1^k)) * (m1 / (sqrt(v)/(float)sqrt(1-beta2^k) + eps))
  * every fp32 operation rounded once (IEEE sqrt and division).
  *
- *   p_in, p_out DEVICE fp32[n]; p_out may equal p_in.
+ *   p_in, p_out DEVICE fp32[n]; p_out may equal p_in.  p_out may be NULL if delta_out
+ *               is given: p' is then only used to form delta_out (the last local
+ *               step of a round whose parameters restart from the next anchor
+ *               need not store x_{t,tau}: 30 bytes per coordinate instead of 34).
  *   grad_bf16   DEVICE uint16[n] (bf16 bit patterns).
  *   exp_avg, exp_avg_sq  DEVICE fp32[n], updated in place.
  *   anchor, delta_out    both NULL, or DEVICE fp32[n]: delta_out = anchor - p'

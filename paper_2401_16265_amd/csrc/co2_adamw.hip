@@ -2,7 +2,9 @@
 // base optimizer; decoupled weight decay as in Loshchilov & Hutter), fp32 master
 // weights and moments, bf16 gradients.  14 bytes read and 12 written per
 // coordinate; optionally also forms the round's pseudo-gradient anchor - p'
-// (the payload of the all-reduce launched after the last inner step) and the
+// (the payload of the all-reduce launched after the last inner step; p' itself
+// then need not be stored, since the next round restarts from the new anchor:
+// p_out = NULL, 8 bytes written) and the
 // per-segment sum of squares of the step p' - p_in (the first inner step's norm
 // is the denominator of the staleness gap, Eq. 3).
 #include "co2_device.hpp"
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(kWave) void adamw_step(
       constexpr int kRowBytes = kWave * 16;
       st4_stream(exp_avg + jb, kRowBytes, lane, make_float4(mc[0], mc[1], mc[2], mc[3]));
       st4_stream(exp_avg_sq + jb, kRowBytes, lane, make_float4(vc[0], vc[1], vc[2], vc[3]));
-      st4_stream(p_out + jb, kRowBytes, lane, make_float4(po[0], po[1], po[2], po[3]));
+      if (p_out) st4_stream(p_out + jb, kRowBytes, lane, make_float4(po[0], po[1], po[2], po[3]));
       if (HAS_DOUT) {
         const float ac[4] = {va[u].x, va[u].y, va[u].z, va[u].w};
         st4_stream(dout + jb, kRowBytes, lane,
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kWave) void adamw_step(
       const float pn = adamw_coord(p, bf16_to_f32(grad[j]), m1, v, h);
       exp_avg[j] = m1;
       exp_avg_sq[j] = v;
-      p_out[j] = pn;
+      if (p_out) p_out[j] = pn;
       if (HAS_DOUT) dout[j] = anchor[j] - pn;
       if (HAS_NORM) acc += sq(pn - p);
     }

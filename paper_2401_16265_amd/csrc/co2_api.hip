@@ -466,7 +466,8 @@ int co2_inner_adamw(int64_t n, const float* p_in, float* p_out, const uint16_t* 
                     float* delta_out, const int64_t* seg_off, const int64_t* seg_off_dev,
                     int32_t S, double* step_sq_out, void* workspace, size_t workspace_bytes,
                     void* hip_stream) {
-  if (n < 1 || !p_in || !p_out || !grad_bf16 || !exp_avg || !exp_avg_sq) return CO2_EINVAL;
+  if (n < 1 || !p_in || !grad_bf16 || !exp_avg || !exp_avg_sq) return CO2_EINVAL;
+  if (!p_out && !delta_out) return CO2_EINVAL;       // p' must go somewhere
   if (adam_step < 1) return CO2_EINVAL;
   if (!std::isfinite(lr) || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) ||
       !(eps >= 0.0f) || !std::isfinite(weight_decay))

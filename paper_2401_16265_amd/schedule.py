@@ -109,6 +109,11 @@ class CO2Worker:
         # Optional stand-in for what produces the gradient of a local step (forward and
         # backward pass): called as inner_compute(k) before local step k, on the main stream.
         self.inner_compute = None
+        # The last local step of a round forms the pseudo-gradient x_{t,0} - x_{t,tau}; x_{t,tau}
+        # itself is read by nothing afterwards (the next round's first step starts from the new
+        # anchor).  With this set the last step does not store it (4 bytes per parameter less);
+        # `params` then holds x_{t,tau-1} after a round (x_{t,0} itself is anchor[t % 2] if tau = 1).
+        self.skip_last_param_store = False
 
     def close(self):
         """Frees a buffer set taken at construction (all work on the buffers has completed)."""
@@ -129,7 +134,8 @@ class CO2Worker:
             if self.inner_compute is not None:
                 self.inner_compute(k)
             co2.co2_inner_adamw(
-                self.n, a_cur if first else self.params, self.params, grads[k], self.exp_avg,
+                self.n, a_cur if first else self.params,
+                None if (last and self.skip_last_param_store) else self.params, grads[k], self.exp_avg,
                 self.exp_avg_sq, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, self.adam_k,
                 anchor=a_cur if last else None, delta_out=self.own[t % 2] if last else None,
                 table=self.table if first else None,

@@ -79,6 +79,39 @@ def test_adamw_parity(dev, n, inplace):
             assert_close(fsn.cpu().numpy(), np.sqrt(out["step_sq"]).astype(np.float32), "sqrt", tol=1e-6)
 
 
+@pytest.mark.parametrize("n", [513, 4099])
+def test_adamw_without_param_store(dev, n):
+    """p_out = NULL with delta_out: the step's p' goes into anchor - p' only; the parameter
+    buffer keeps its bits, everything else equals the oracle's step."""
+    table = ADAM_TABLES[n]
+    seg = co2.SegmentTable(table, dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    p = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(3, 1))
+    anchor = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(3, 2))
+    m1 = co2_inputs.fill_normal_(torch.empty(n, **f32), 1e-3, co2_inputs.seed_for(3, 3))
+    v = co2_inputs.fill_normal_(torch.empty(n, **f32), 1e-3, co2_inputs.seed_for(3, 4)).square_()
+    g = co2_inputs.fill_bf16_normal_(torch.empty(n, dtype=torch.bfloat16, device=dev), 1e-3,
+                                     co2_inputs.seed_for(3, 10))
+    dout = torch.empty(n, **f32)
+    sq = torch.empty(seg.S, dtype=torch.float64, device=dev)
+    ws = torch.empty(co2.workspace_bytes(n, seg.S, 1), dtype=torch.uint8, device=dev)
+    o_p, o_m1, o_v, o_anchor = p.cpu().numpy(), m1.cpu().numpy(), v.cpu().numpy(), anchor.cpu().numpy()
+    p_before = p.clone()
+    co2.co2_inner_adamw(n, p, None, g, m1, v, adam_step=7, anchor=anchor, delta_out=dout, table=seg,
+                        step_sq_out=sq, workspace=ws, **HP)
+    o_out = np.empty_like(o_p)
+    out = co2_oracle.adamw_f32(p_in=o_p, p_out=o_out, grad_bf16=bits(g), exp_avg=o_m1, exp_avg_sq=o_v, k=7,
+                               anchor=o_anchor, seg_off=table, want_step_sq=True, **HP)
+    assert torch.equal(p, p_before), "the parameter buffer was written"
+    assert_close(m1.cpu().numpy(), o_m1, "exp_avg")
+    assert_close(v.cpu().numpy(), o_v, "exp_avg_sq")
+    assert_close(dout.cpu().numpy(), out["dout"], "delta_out")
+    assert_close(sq.cpu().numpy(), out["step_sq"], "step_sq", tol=1e-12)
+    # p' has to go somewhere
+    rc = co2.co2_inner_adamw(n, p, None, g, m1, v, adam_step=8, check=False, **HP)
+    assert rc == co2.CO2_EINVAL
+
+
 class OracleWorker:
     """The same round, step by step, through the CPU oracle on sampled segments."""
 
@@ -128,7 +161,7 @@ class OracleWorker:
         self.t += 1
 
 
-def run_rounds(dev, table, sample, K, tau, rounds, seed, phi, buffer_set=False):
+def run_rounds(dev, table, sample, K, tau, rounds, seed, phi, buffer_set=False, skip_store=False):
     seg = co2.SegmentTable(table, dev)
     n = seg.n
     f32 = dict(dtype=torch.float32, device=dev)
@@ -136,6 +169,7 @@ def run_rounds(dev, table, sample, K, tau, rounds, seed, phi, buffer_set=False):
     mk = lambda bs: CO2Worker(seg, K, tau, 1.0, 0.9, phi, 1.0, AdamWConfig(**HP), dev, init,  # noqa: E731
                               buffer_set=bs)
     w_ov, w_se = mk(buffer_set), mk(False)
+    w_ov.skip_last_param_store = skip_store      # the serial worker keeps storing x_{t,tau}
     ow = OracleWorker(table, sample, K, tau, 1.0, 0.9, phi, 1.0, init)
     grads = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(tau)]
     for t in range(rounds):
@@ -150,13 +184,17 @@ def run_rounds(dev, table, sample, K, tau, rounds, seed, phi, buffer_set=False):
         ow.round(grads, w_ov.peers)
         torch.cuda.synchronize()
         # overlapped == serial, bit for bit
-        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam"):
+        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam")[1 if skip_store else 0:]:
             assert torch.equal(getattr(w_ov, name), getattr(w_se, name)), f"{name}: overlap != serial"
+        if skip_store:
+            # x_{t,tau} was really not stored (and nothing that is read later depended on it)
+            assert not torch.equal(w_ov.params, w_se.params)
         for i in range(2):
             assert torch.equal(w_ov.anchor[i], w_se.anchor[i]) and torch.equal(w_ov.own[i], w_se.own[i])
         # against the oracle (sampled segments)
         nxt = w_ov.anchor[(t + 1) % 2]
-        assert_close(ow.gather(w_ov.params), ow.params, "params")
+        if not skip_store:
+            assert_close(ow.gather(w_ov.params), ow.params, "params")
         assert_close(ow.gather(w_ov.exp_avg), ow.exp_avg, "exp_avg")
         assert_close(ow.gather(w_ov.exp_avg_sq), ow.exp_avg_sq, "exp_avg_sq")
         assert_close(ow.gather(w_ov.momentum), ow.momentum, "momentum")
@@ -186,6 +224,16 @@ def test_overlapped_rounds_in_a_buffer_set(dev):
 def test_overlapped_rounds_tau_one(dev):
     table = [0, 5, 4096, 10001]
     run_rounds(dev, table, [0, 1, 2], K=2, tau=1, rounds=4, seed=5, phi=1.0)
+
+
+@pytest.mark.parametrize("tau", [1, 3])
+def test_rounds_without_the_last_parameter_store(dev, tau):
+    """The last local step given p_out = NULL (its x_{t,tau} only feeds the pseudo-gradient):
+    moments, momentum, anchors, pseudo-gradients and Lambda keep the bits of the worker that
+    stores it, and match the oracle."""
+    table = co2_inputs.gpt_table(layers=2, d=65, ffn=257, vocab=1001, ctx=33)
+    run_rounds(dev, table, list(range(len(table) - 1)), K=4, tau=tau, rounds=5, seed=21, phi=1e-3,
+               skip_store=True)
 
 
 class StreamedOracleWorker:
@@ -307,8 +355,11 @@ def test_overlapped_rounds_350m(dev):
         w_ov.round_overlapped(grads)
         w_se.round_serial(grads)
         torch.cuda.synchronize()
-        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam"):
+        for name in ("params", "exp_avg", "exp_avg_sq", "momentum", "lam")[1 if skip_store else 0:]:
             assert torch.equal(getattr(w_ov, name), getattr(w_se, name)), f"{name}: overlap != serial"
+        if skip_store:
+            # x_{t,tau} was really not stored (and nothing that is read later depended on it)
+            assert not torch.equal(w_ov.params, w_se.params)
         for i in range(2):
             assert torch.equal(w_ov.anchor[i], w_se.anchor[i]) and torch.equal(w_ov.own[i], w_se.own[i])
         res = ow.round_and_compare(grads, w_ov.peers, w_ov, w_ov.anchor[(t + 1) % 2])

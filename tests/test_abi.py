@@ -168,6 +168,7 @@ def test_norms_and_adamw_reject_bad_arguments():
     assert adam(m=_fake(0)) == co2.CO2_EINVAL                         # exp_avg on the params
     assert adam(p_out=_fake(0) + 64) == co2.CO2_EINVAL                # partial overlap p_in/p_out
     assert adam(sq=_fake(5)) == co2.CO2_EINVAL                        # norm without a table
+    assert adam(p_out=None) == co2.CO2_EINVAL                         # p' stored nowhere (no delta_out either)
     assert adam(sq=_fake(5), seg=keep.ctypes.data, segd=_fake(20), S=2, ws=_fake(8), wsb=16) == co2.CO2_EWORKSPACE
     assert L.co2_sqrt_to_f32(None, _fake(1), 4, None) == co2.CO2_EINVAL
     assert L.co2_copy_f32(_fake(0), _fake(0), 16, None) == co2.CO2_EINVAL

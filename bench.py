@@ -77,6 +77,9 @@ def parse():
                     help="350m_overlap only: run about this many TFLOP of bf16 GEMMs before each local step "
                          "as a compute-bound stand-in for the forward/backward pass (0 = none: the round is "
                          "then HBM-bound on both streams)")
+    ap.add_argument("--own-in-place", action="store_true",
+                    help="delta_out overwrites deltas[0] in place (one buffer for the worker's own "
+                         "pseudo-gradient instead of a ping-pong pair)")
     ap.add_argument("--store-last-params", action="store_true",
                     help="350m_overlap only: the last local step of a round also stores x_{t,tau} "
                          "(4 more bytes per parameter; nothing reads it)")
@@ -338,6 +341,8 @@ def main():
         """One outer step of round t on stream `on` (default: the current stream)."""
         a, m, x, own, peers = bufs
         cur, nxt = own[t % 2], own[(t + 1) % 2]          # deltas[0] = last round's delta_out
+        if args.own_in_place:
+            cur = nxt = own[0]
         flags = (co2.CO2_FLAG_CARRIED_NORMS if (carried and t >= 2) else 0) | vflags
         p = co2.make_params(seg, K, cfg.alpha, cfg.beta, cfg.phi, cfg.c, cfg.tau, t, flags,
                             ev[0] if ev else None, ev[1] if ev else None,
@@ -407,7 +412,7 @@ def main():
 
     co2_inputs.fill_normal_(a, cfg.param_std, co2_inputs.seed_for(cfg.seed, 1))
     co2_inputs.fill_normal_(m, cfg.momentum_std, co2_inputs.seed_for(cfg.seed, 2))
-    drift(own[1], 99)                                       # own pseudo-gradient of the round before round 1
+    drift(own[0 if args.own_in_place else 1], 99)           # own pseudo-gradient of the round before round 1
     torch.cuda.synchronize()
 
     step_no = [1]

@@ -191,8 +191,11 @@ size_t co2_workspace_bytes(int64_t n, int32_t S, int32_t K);
  * x' = anchor[j] - alpha*(m'*scale), M2 = sum_j momentum_in[j]^2 and the
  * numerator of Lambda is alpha*min(sqrt(M2), phi) (NORM_CLIP).
  *
- * Buffers must not overlap except anchor_out == anchor (no output, small or
- * large, may overlap any other argument or the workspace).  Errors: CO2_EINVAL
+ * Buffers must not overlap, with two exceptions: anchor_out == anchor, and
+ * delta_out == deltas[0] (the worker's own pseudo-gradient replaced in place,
+ * one buffer instead of a ping-pong pair: each coordinate's old value is read
+ * before the new one is stored).  No other output, small or large, may overlap
+ * any other argument or the workspace.  Errors: CO2_EINVAL
  * for NULL/misaligned/overlapping buffers, n<1, S<1, K outside 1..CO2_MAX_K, a
  * bad segment table, beta outside [0,1), phi<=0 or NaN, c<0, tau<1, step<0,
  * non-finite alpha, unknown or inconsistent flags, pull_rho outside (0,1],

@@ -281,8 +281,11 @@ int outer_step_impl(const co2_params* p, float* params, const float* anchor, flo
       const void* dk = deltas[k];
       if (!dk || !aligned16(dk)) return CO2_EINVAL;
       // inputs may repeat among themselves, but no output may touch them
+      // (delta_out may BE deltas[0]: each coordinate's old value is read before the new one
+      // is stored, by the same lane)
+      const bool in_place_own = k == 0 && dk == delta_out;
       if (overlaps(dk, db, params, nb) || overlaps(dk, db, momentum, nb) ||
-          overlaps(dk, db, delta_out, db) || overlaps(dk, db, anchor_out, nb) ||
+          (!in_place_own && overlaps(dk, db, delta_out, db)) || overlaps(dk, db, anchor_out, nb) ||
           overlaps(dk, db, lambda_out, sb) || overlaps(dk, db, p->clipped_out, cb))
         return CO2_EINVAL;
       dptr.p[nbuf++] = dk;

@@ -180,6 +180,52 @@ def test_carried_norms_equal_two_pass(dev):
         assert torch.equal(hs[0].m, hs[1].m) and torch.equal(hs[0].a, hs[1].a)
 
 
+@pytest.mark.parametrize("transport", ["f32", "bf16", "f16"])
+def test_own_pseudo_gradient_updated_in_place(dev, transport):
+    """delta_out == deltas[0]: one buffer for the worker's own pseudo-gradient.  Every output
+    keeps the bits of the run with a ping-pong pair (which the other tests compare with the
+    oracle), over four rounds, the last two in the carried form; tiles with segment boundaries
+    and a ragged end included."""
+    table = [0, 5, 5, 1300, 70000, 100003]
+    n, S, K = table[-1], len(table) - 1, 3
+    seg = co2.SegmentTable(table, dev)
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[transport]
+    entry = {"f32": co2.co2_outer_step, "bf16": co2.co2_outer_step_bf16, "f16": co2.co2_outer_step_f16}[transport]
+    f32 = dict(dtype=torch.float32, device=dev)
+
+    def run(in_place):
+        a = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(9, 1))
+        m = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(9, 2))
+        x = torch.empty(n, **f32)
+        own = [torch.zeros(n, dtype=tdt, device=dev) for _ in range(1 if in_place else 2)]
+        lam = torch.empty(S, **f32)
+        ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
+        outs = []
+        for t in range(4):
+            co2_inputs.fill_student_t_(x, 1e-3, 3, co2_inputs.seed_for(9, 100, t))
+            x.add_(a)
+            peers = [co2_inputs.fill_normal_(torch.empty(n, **f32), 1e-3, co2_inputs.seed_for(9, 200 + k, t)).to(tdt)
+                     for k in range(K - 1)]
+            cur, nxt = (own[0], own[0]) if in_place else (own[t % 2], own[(t + 1) % 2])
+            p = co2.make_params(seg, K, 1.0, 0.9, 2e-3, 1.0, 4, t, co2.CO2_FLAG_CARRIED_NORMS if t >= 2 else 0)
+            entry(p, x, a, a, m, [cur] + peers, nxt, None, lam, ws)
+            torch.cuda.synchronize()
+            outs.append([v.clone() for v in (x, a, m, nxt.view(torch.int16) if tdt != torch.float32 else nxt, lam)])
+        return outs
+
+    for t, (got, want) in enumerate(zip(run(True), run(False))):
+        for name, g, w in zip(("params", "anchor", "momentum", "delta_out", "Lambda"), got, want):
+            assert torch.equal(g, w), f"round {t}: {name} differs when delta_out overwrites deltas[0]"
+    # partial overlap is still refused
+    a = torch.zeros(n + 64, **f32)
+    p = co2.make_params(seg, 1, 1.0, 0.9, 1.0, 1.0, 4, 1, 0)
+    ws = torch.empty(co2.workspace_bytes(n, S, 1), dtype=torch.uint8, device=dev)
+    buf = torch.zeros(n + 64, **f32)
+    rc = co2.co2_outer_step(p, torch.zeros(n, **f32), a[:n], a[:n], torch.zeros(n, **f32), [buf[:n]], buf[4:n + 4],
+                            None, torch.empty(S, **f32), ws, check=False)
+    assert rc == co2.CO2_EINVAL
+
+
 def test_resume_from_saved_state(dev):
     """Checkpoint/resume: the state that defines a round is anchor, momentum, the
     in-flight pseudo-gradients and the round index.  Restoring it into fresh

@@ -109,7 +109,8 @@ def test_outer_step_rejects_bad_buffers():
     assert _call(p, params=_fake(0) + 4) == co2.CO2_EINVAL            # misaligned
     assert _call(p, deltas=(_fake(3) + 8, _fake(4))) == co2.CO2_EINVAL
     assert _call(p, momentum=_fake(0) + 1024) == co2.CO2_EINVAL       # overlaps params
-    assert _call(p, delta_out=_fake(3)) == co2.CO2_EINVAL             # output on a delta
+    assert _call(p, delta_out=_fake(4)) == co2.CO2_EINVAL             # output on a peer's delta
+    assert _call(p, delta_out=_fake(3) + 16) == co2.CO2_EINVAL        # partly on deltas[0] (all of it is allowed)
     assert _call(p, anchor_out=_fake(1) + 16) == co2.CO2_EINVAL       # partial overlap with anchor
     assert _call(p, deltas=(_fake(2), _fake(4))) == co2.CO2_EINVAL    # delta is the momentum
     assert _call(p, ws=None) == co2.CO2_EWORKSPACE
@@ -132,7 +133,7 @@ def test_static_entry_point_validates_like_the_workspace_one():
     assert call(p) == co2.CO2_EINVAL
     p, keep = _params([0, 1000, 4096])
     assert call(p, momentum=_fake(0) + 1024) == co2.CO2_EINVAL
-    assert call(p, delta_out=_fake(3)) == co2.CO2_EINVAL
+    assert call(p, delta_out=_fake(4)) == co2.CO2_EINVAL
     # sizes whose partial sums do not fit the static scratch array
     big = 200_000_000
     assert co2.workspace_bytes(big, 2, 2) > co2.CO2_STATIC_SCRATCH_BYTES

@@ -207,7 +207,10 @@ class StreamedOuterStepHarness:
                  momentum_std: float = 0.02, start_step: int = 1, bf16: bool = False,
                  transport: Optional[str] = None, chunk_elems: int = 1 << 26, workers: int = 8,
                  nonstale: bool = False, norm_clip: bool = False, pull_rho: float = 1.0,
-                 use_first_step_norm: bool = False):
+                 use_first_step_norm: bool = False, buffer_set: bool = False):
+        """buffer_set: the flat device buffers come from one co2.BufferSet with the default piece
+        size, in bench.py's order (anchor, momentum, params, own x 2, peers) -- the layout the
+        bench times -- instead of separate plain allocations; close() frees it."""
         self.nonstale, self.norm_clip, self.pull_rho = nonstale, norm_clip, pull_rho
         self.variant = nonstale or norm_clip or pull_rho != 1.0
         self.table = [int(o) for o in table]
@@ -225,10 +228,18 @@ class StreamedOuterStepHarness:
         f32 = dict(dtype=torch.float32, device=device)
         dd = dict(dtype={"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.transport],
                   device=device)
-        self.x, self.a, self.m = (torch.empty(n, **f32) for _ in range(3))
+        self._set = None
+        if buffer_set:
+            esz = 2 if bf16 else 4
+            self._set = co2.BufferSet([4 * n] * 3 + [esz * n] * (K + 1), 0, device)
+            self.a, self.m, self.x = (v.view(torch.float32) for v in self._set.views[:3])
+            flat = [v.view(dd["dtype"]).zero_() for v in self._set.views[3:]]
+            self.own, self.peers = flat[:2], flat[2:]
+        else:
+            self.x, self.a, self.m = (torch.empty(n, **f32) for _ in range(3))
+            self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]
+            self.peers = [torch.zeros(n, **dd) for _ in range(K - 1)]
         self.noise = torch.empty(n, **f32)          # this round's local drift (an input of both sides)
-        self.own = [torch.zeros(n, **dd), torch.zeros(n, **dd)]
-        self.peers = [torch.zeros(n, **dd) for _ in range(K - 1)]
         self.lam = torch.empty(self.S, **f32)
         self.clipped = torch.full((self.S,), -1, dtype=torch.int64, device=device)
         self.ws = torch.empty(co2.workspace_bytes(n, self.S, K), dtype=torch.uint8, device=device)
@@ -264,6 +275,14 @@ class StreamedOuterStepHarness:
             finally:
                 self.sets.put(st)
         for_each_chunk(self.ch, init, workers)
+
+    def close(self):
+        """Frees the buffer set, if the buffers were taken from one (all work on them has finished)."""
+        if self._set is not None:
+            torch.cuda.synchronize()
+            self.x = self.a = self.m = self.own = self.peers = None
+            self._set.close()
+            self._set = None
 
     def _fill_drift(self, t: torch.Tensor, buffer_id: int):
         sd = co2_inputs.seed_for(self.seed, buffer_id, self.t)

@@ -153,18 +153,20 @@ def test_bf16_deltas_edge_shapes(dev, name, K):
 def test_bf16_deltas_1p3b_every_element(dev):
     """Headline-size buffers with bf16 pseudo-gradient transport (42 B/param): every
     element of every output and every Lambda against the oracle, three consecutive
-    rounds, the last one in the carried (single-pass) form."""
+    rounds, the last one in the carried (single-pass) form; buffers in one buffer set as
+    in the bench."""
     cfg = co2_inputs.CONFIGS["1p3b"]
     table = co2_inputs.config_table(cfg)
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
     h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed, drift="student_t",
                                  drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
-                                 momentum_std=cfg.momentum_std, start_step=1, bf16=True)
+                                 momentum_std=cfg.momentum_std, start_step=1, bf16=True, buffer_set=True)
     assert h.ch.n == 1_343_868_928
     for i in range(3):
         res = h.step(flags=co2.CO2_FLAG_CARRIED_NORMS if i >= 2 else 0)
         print(f"  1p3b bf16 step {h.t - 1}: {res}", flush=True)
     assert res["lam_max"] > 1.0
+    h.close()
 
 
 def test_carried_norms_equal_two_pass(dev):
@@ -338,7 +340,8 @@ def test_gpt2_small_ten_steps(dev):
 def test_1p3b_headline_every_element_twenty_steps(dev):
     """The headline workload as stated: 1 343 868 928 parameters in 292 segments,
     K=8, Student-t drift, 20 consecutive outer rounds in the launch configuration
-    the bench times (carried norms after the first two rounds).  EVERY element of
+    the bench times (carried norms after the first two rounds; the flat buffers in one
+    buffer set with 64 MiB pieces, in the bench's order).  EVERY element of
     params, anchor, momentum and delta_out and every Lambda and clipped count of
     every round is compared with the oracle, which carries its own full state."""
     cfg = co2_inputs.CONFIGS["1p3b"]
@@ -347,7 +350,7 @@ def test_1p3b_headline_every_element_twenty_steps(dev):
     hp = HP(K=cfg.K, alpha=cfg.alpha, beta=cfg.beta, phi=cfg.phi, c=cfg.c, tau=cfg.tau)
     h = StreamedOuterStepHarness(table, hp, dev, seed=cfg.seed, drift="student_t",
                                  drift_scale=cfg.drift_scale, drift_nu=cfg.drift_nu,
-                                 momentum_std=cfg.momentum_std, start_step=1)
+                                 momentum_std=cfg.momentum_std, start_step=1, buffer_set=True)
     assert h.ch.n == table[-1] and len(h.ch.sample) == 292
     clipped_steps, lam_max = 0, 1.0
     for i in range(cfg.steps):
@@ -372,6 +375,8 @@ def test_1p3b_headline_every_element_twenty_steps(dev):
     assert_close(got[0], co2_oracle.sqnorms(h.o_own, table), "sum of d0^2, all segments", tol=1e-9)
     assert_close(got[1], co2_oracle.sqnorms(h.o_m, table, phi=hp.phi),
                  "sum of Clip(m)^2, all segments", tol=1e-9)
+    del own
+    h.close()
 
 
 # ------------------------------------------------------------------ more than 2^31 elements

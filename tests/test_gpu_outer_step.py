@@ -200,7 +200,7 @@ def test_own_pseudo_gradient_updated_in_place(dev, transport):
         m = co2_inputs.fill_normal_(torch.empty(n, **f32), 0.02, co2_inputs.seed_for(9, 2))
         x = torch.empty(n, **f32)
         own = [torch.zeros(n, dtype=tdt, device=dev) for _ in range(1 if in_place else 2)]
-        lam = torch.empty(S, **f32)
+        lam = torch.ones(S, **f32)                 # round 0 writes no Lambda
         ws = torch.empty(co2.workspace_bytes(n, S, K), dtype=torch.uint8, device=dev)
         outs = []
         for t in range(4):

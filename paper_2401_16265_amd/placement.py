@@ -4,27 +4,31 @@ The fused sweep streams 3 + K + 1 flat buffers in lock step.  On MI355X its
 duration depends on how those streams fall onto HBM channels and banks relative
 to each other, which is decided by the physical pages behind the buffers.
 Measured at 1.3B parameters, K = 8: the same kernel on the same data runs
-between 11.9 and 13.4 ms depending on the allocation it was given (a
+between 11.8 and 13.4 ms depending on the allocation it was given (a
 single-stream copy runs equally fast in all of them; the byte gap between
 consecutive buffers moves it by another +-1.5 %), and what the driver hands out
-depends on the allocation history of the machine.  None of this can be predicted
-from user space, but it is stable for the life of an allocation, and a training
-job allocates once.  So the driver's free memory is first brought back to one
-block (compact_device_memory) and the layout is then chosen by measurement.
-Candidates are
+for a plain allocation depends on the allocation history of the machine.  It is
+stable for the life of an allocation, and a training job allocates once.
 
+Two kinds of layout are made here:
+
+  * piece-major buffer sets (co2_buffer_set_create): every buffer's physical
+    memory is obtained in pieces, piece j of all buffers before piece j+1, so
+    that what the sweep touches at one time lies close together.  With 64 MiB
+    pieces they have been at the fast end in every set made, on every machine
+    state tried; this is the layout to use, taken as it comes (candidates=0:
+    nothing is compared by timing);
   * plain single allocations with the buffers carved out back to back, made in
     turn while earlier ones are still held, so that each lands on other physical
-    pages, each tried with a few gaps between consecutive buffers;
-  * on request, piece-major buffer sets (co2_buffer_set_create): every buffer's
-    physical memory is obtained in pieces, piece j of all buffers before piece
-    j+1, so that what the sweep touches at one time lies close together.  They
-    have been at the fast end on every machine state tried, but allocating and
-    freeing piece-sized blocks leaves the driver's free memory more scattered
-    for whoever allocates next, so they are not tried by default.
+    pages, each tried with a few gaps between consecutive buffers.  The caller's
+    probe -- a few launches of the real kernel -- is timed on every candidate and
+    the fastest is kept; everything else is freed.  Kept for comparison with the
+    buffer sets: one such allocation in three is slow, and on a machine whose
+    memory has seen many allocate/free cycles all of them are.
 
-The caller's probe -- a few launches of the real kernel -- is timed on every
-candidate and the fastest is kept; everything else is freed.
+compact_device_memory (opt-in: it briefly takes nearly all free memory of the
+device, so only for a process that has the GPU to itself) first brings the
+driver's free memory back to one block.
 
 This module holds host logic only (allocation, slicing, timing decisions); the
 probe it is given runs the library's kernels.

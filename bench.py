@@ -490,7 +490,8 @@ def main():
     ce.synchronize()
     copy_gbps = 8 * n * 5 / (cb.elapsed_ms(ce) * 1e-3) / 1e9
 
-    traffic_key = (cfg.name, args.deltas, K)
+    # a profiled constant exists only for Algorithm 1 in the carried form (what the profile ran)
+    traffic_key = (cfg.name, args.deltas, K) if (not variant and carried) else None
     out = {
         "metric": "outer-step params/sec",
         "value": n / (ms_per_step * 1e-3),

@@ -28,7 +28,8 @@
  *     graph (leave the timing events of co2_params NULL then): `step` only
  *     tells the first round from the later ones, so two captured steady-state
  *     rounds -- the two halves of a delta_out ping-pong -- can be replayed for
- *     the rest of a run.
+ *     the rest of a run (one captured round suffices when delta_out is
+ *     deltas[0] itself).
  *   - Every DEVICE buffer must be 16-byte aligned.  Layout advice: the sweep
  *     streams all flat buffers of one worker (params, anchor, momentum, the K
  *     pseudo-gradient buffers, delta_out) in lock step, and on MI355X its
@@ -137,9 +138,9 @@ typedef struct co2_params {
                                  step 0).  Costs two small extra launches when set.       */
   float pull_rho;             /* CO2_FLAG_ANCHOR_PULL: rho in (0,1]; ignored otherwise     */
   int32_t sweep_waves_per_cu; /* tuning: resident wavefronts per compute unit the sweep kernel
-                                 is capped to; 0 = the library's measured default (4..8 by K).
-                                 Lower it (2..4) for a sweep that shares the GPU with another
-                                 bandwidth-bound kernel on a second stream.  Range 0..32.  */
+                                 is capped to; 0 = the library's measured default (5..8 by K),
+                                 which was also the fastest beside another bandwidth-bound
+                                 kernel on a second stream.  Range 0..32.                 */
 } co2_params;
 
 /* Bytes of DEVICE workspace the calls below need for these sizes (256-byte

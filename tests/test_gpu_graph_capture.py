@@ -114,3 +114,49 @@ def test_graph_replays_match_eager_and_oracle():
     del g
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_one_captured_round_with_the_own_pseudo_gradient_in_place():
+    """delta_out == deltas[0] removes the ping-pong, so ONE captured steady-state round can be
+    replayed for the rest of a run: six replays (inputs refreshed eagerly in between) against the
+    eager ping-pong twin, bit for bit."""
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    dev = torch.device("cuda:0")
+    table = [0, 1000, 1000, 70001, 131072, 200003]
+    n = table[-1]
+    f32 = dict(dtype=torch.float32, device=dev)
+    noise = torch.empty(n, **f32)
+    peers = [torch.empty(n, **f32) for _ in range(K - 1)]
+
+    def refresh(t):
+        co2_inputs.fill_normal_(noise, 1e-3, co2_inputs.seed_for(6, 100, t))
+        for k, pb in enumerate(peers):
+            co2_inputs.fill_normal_(pb, 1e-3, co2_inputs.seed_for(6, 200 + k, t))
+
+    eager, graphed = State(table, dev, 6), State(table, dev, 6)
+    graphed.own = [graphed.own[0], graphed.own[0]]              # one buffer: read as deltas[0], then overwritten
+    main = torch.cuda.current_stream().cuda_stream
+    for t in range(2):
+        refresh(t)
+        for st in (eager, graphed):
+            st.round(t, noise, peers, main)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=side):
+        graphed.round(2, noise, peers, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for t in range(2, 8):
+        print(f"  in-place graph replay for round {t}", flush=True)
+        refresh(t)
+        torch.cuda.synchronize()
+        g.replay()
+        eager.round(t, noise, peers, main)
+        torch.cuda.synchronize()
+        for name in ("x", "a", "m", "lam"):
+            assert torch.equal(getattr(eager, name), getattr(graphed, name)), f"round {t}: {name} differs"
+        assert torch.equal(eager.own[(t + 1) % 2], graphed.own[0]), f"round {t}: delta_out differs"
+    assert float(eager.lam.max()) > 1.0
+    del g
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -55,8 +55,12 @@ struct AdamArgs {
 // placements: about 56-64 KB of loads in flight per compute unit.  A sweep
 // wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront 4 KB
 // per buffer, an AdamW wavefront 7 KB (9 KB with the anchor).
-inline int default_sweep_waves(int delta_streams) {
-  return delta_streams <= 4 ? 8 : delta_streams <= 9 ? 7 : 6;   // 11 and more: two load phases, see co2_sweep.hip
+// `delta_kb`: KB of pseudo-gradient loads one sweep wavefront issues (1 per fp32 buffer, 0.5 per
+// 16-bit buffer), beside its 3 KB of anchor, momentum and params.
+inline int default_sweep_waves(float delta_kb) {
+  if (delta_kb <= 0.5f) return 12;                 // K = 1 with 16-bit transport
+  if (delta_kb <= 1.0f) return 10;                 // K = 1, or K = 2 with 16-bit transport
+  return delta_kb <= 4.0f ? 8 : delta_kb <= 9.0f ? 7 : 6;   // 11 and more: two load phases, see co2_sweep.hip
 }
 constexpr int kNormWavesOneBuffer = 16;
 constexpr int kNormWavesTwoBuffers = 8;

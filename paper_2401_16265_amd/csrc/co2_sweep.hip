@@ -376,12 +376,14 @@ __global__ __launch_bounds__(kWave) void copy_f32(const float* __restrict__ src,
 template <int NB, bool HAS_X, int DT>
 static hipError_t launch_sweep_v(const SweepArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kSweepTile - 1) / kSweepTile);
-  // 16-bit pseudo-gradients put half the bytes per stream in flight: cap like NB/2 fp32 streams.
+  // 16-bit pseudo-gradients put half the bytes per stream in flight: two of them count as one
+  // fp32 stream (K = 1 and 2 apart, which run fastest with more wavefronts: measured at 1.3B,
+  // 12 at K = 1 and 10 at K = 2 against 8: +8 % and +3 %).
   // Kernels with two load phases hold at most ~11 KB in flight per wavefront like K = 8, but run
   // fastest with slightly fewer wavefronts (measured at 1.3B: 6 at K = 12, 5 at K = 16).
   constexpr bool kTwoPhase = phase_a_buffers<NB, DT>() < NB;
-  const int streams = DT == kDeltaF32 ? NB : (NB + 1) / 2;
-  const int dflt = !kTwoPhase ? default_sweep_waves(streams) : NB > 12 ? 5 : 6;
+  const float delta_kb = DT == kDeltaF32 ? float(NB) : NB <= 2 ? 0.5f * float(NB) : float((NB + 1) / 2);
+  const int dflt = !kTwoPhase ? default_sweep_waves(delta_kb) : NB > 12 ? 5 : 6;
   const unsigned lds = throttle_lds_bytes(g.waves_per_cu > 0 ? g.waves_per_cu : dflt);
   const SweepScalars h{g.alpha, g.beta, g.phi, g.rK};
   hipLaunchKernelGGL((fused_sweep<NB, HAS_X, DT>), dim3(tiles), dim3(kWave), lds, st, g.x, g.a_in,

@@ -219,7 +219,7 @@ int co2_outer_step(const co2_params* p,
  * (make that call outside a graph capture), later calls only enqueue kernels.
  *
  *   - Limit: co2_workspace_bytes(p->n, p->S, p->K) <= CO2_STATIC_SCRATCH_BYTES
- *     (about 1.7e8 elements with a few hundred segments); beyond it the call
+ *     (about 1.3e8 elements with a few hundred segments); beyond it the call
  *     returns CO2_ESCRATCH before anything is enqueued.
  *   - The GPU that hip_stream belongs to must be the current device.
  *   - All calls on one GPU share that GPU's array, which keeps what the last

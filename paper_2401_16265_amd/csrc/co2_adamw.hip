@@ -136,7 +136,7 @@ hipError_t launch_adamw(const AdamArgs& g, hipStream_t st) {
   const unsigned tiles = static_cast<unsigned>((g.n + kAdamTile - 1) / kAdamTile);
   const AdamScalars h{g.beta1, g.beta2, g.omb1, g.omb2, g.decay, g.step_size, g.sqrt_bc2, g.eps};
   const bool has_dout = g.dout != nullptr, has_norm = g.slots != nullptr;
-  const unsigned lds = throttle_lds_bytes(has_dout ? kAdamWavesWithAnchor : kAdamWavesPerCu);
+  const unsigned lds = throttle_lds_bytes(!has_dout ? kAdamWavesPerCu : g.p_out ? kAdamWavesWithAnchor : kAdamWavesNoStore);
 #define CO2_ADAM_LAUNCH(D, N)                                                              \
   hipLaunchKernelGGL((adamw_step<D, N>), dim3(tiles), dim3(kWave), lds, st, g.n, g.p_in,   \
                      g.p_out, g.grad, g.exp_avg, g.exp_avg_sq, h, g.anchor, g.dout,        \

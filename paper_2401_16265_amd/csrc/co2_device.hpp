@@ -22,10 +22,12 @@ namespace co2 {
 constexpr int kWave = 64;                          // lanes per wavefront = threads per workgroup
 constexpr int kSweepU = 1;                         // 16-byte vectors per lane and stream, fused sweep
 constexpr int kNormU = 4;                          // ... norm pass
-constexpr int kAdamU = 2;                          // ... AdamW step
+constexpr int kAdamU = 1;                          // ... AdamW step (two per lane cost 9-11 %: the step's
+                                                   // IEEE square root and divisions keep a wavefront busy
+                                                   // for about as long as its loads take, with nothing in flight)
 constexpr int64_t kSweepTile = int64_t(kWave) * 4 * kSweepU;   // 256 elements
 constexpr int64_t kNormTile = int64_t(kWave) * 4 * kNormU;     // 1024 elements
-constexpr int64_t kAdamTile = int64_t(kWave) * 4 * kAdamU;     // 512 elements
+constexpr int64_t kAdamTile = int64_t(kWave) * 4 * kAdamU;     // 256 elements
 constexpr int kLdsPerCu = 160 * 1024;              // gfx950 LDS per compute unit
 constexpr int kReduceBlock = 256;                  // threads of the small reduction kernels
 constexpr int kReduceWaves = kReduceBlock / kWave;

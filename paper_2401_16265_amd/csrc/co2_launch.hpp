@@ -54,7 +54,7 @@ struct AdamArgs {
 // Measured optima on MI355X at 1.3B parameters, averaged over several buffer
 // placements: about 56-64 KB of loads in flight per compute unit.  A sweep
 // wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront 4 KB
-// per buffer, an AdamW wavefront 7 KB (9 KB with the anchor).
+// per buffer, an AdamW wavefront 3.5 KB (4.5 KB with the anchor).
 // `delta_kb`: KB of pseudo-gradient loads one sweep wavefront issues (1 per fp32 buffer, 0.5 per
 // 16-bit buffer), beside its 3 KB of anchor, momentum and params.
 inline int default_sweep_waves(float delta_kb) {
@@ -64,8 +64,9 @@ inline int default_sweep_waves(float delta_kb) {
 }
 constexpr int kNormWavesOneBuffer = 16;
 constexpr int kNormWavesTwoBuffers = 8;
-constexpr int kAdamWavesPerCu = 7;
-constexpr int kAdamWavesWithAnchor = 5;   // the step that also reads the anchor and writes delta_out
+constexpr int kAdamWavesPerCu = 16;
+constexpr int kAdamWavesWithAnchor = 12;  // the step that also reads the anchor and writes delta_out
+constexpr int kAdamWavesNoStore = 10;     // ... and does not store the parameters
 constexpr int kCopyWavesPerCu = 7;
 constexpr int kApplyWavesPerCu = 16;      // deferred outer iterate: 2-3 KB of loads per wavefront
 // Records `e` as this thread's most recent HIP error (what co2_last_hip_error() returns).

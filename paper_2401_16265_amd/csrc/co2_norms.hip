@@ -95,6 +95,31 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
   }
 }
 
+// a += rec[t].v[col] (and b += rec[t].v[col + 1] with `two`) for t = first, first + kReduceBlock,
+// ... <= last, in that order.  The records of kSlotBatch steps are loaded before the first of them
+// is added, so that a thread has several loads in flight instead of one (a long segment is
+// otherwise a chain of dependent memory latencies); a step beyond `last` contributes +0.0, which
+// changes no sum of squares.
+constexpr int kSlotBatch = 8;
+__device__ __forceinline__ void add_slots(const SlotRec* __restrict__ rec, int col, bool two,
+                                          int64_t first, int64_t last, double& a, double& b) {
+  for (int64_t t = first; t <= last; t += int64_t(kSlotBatch) * kReduceBlock) {
+    double va[kSlotBatch], vb[kSlotBatch];
+#pragma unroll
+    for (int u = 0; u < kSlotBatch; ++u) {
+      const int64_t tt = t + int64_t(u) * kReduceBlock;
+      const bool in = tt <= last;
+      va[u] = in ? rec[tt].v[col] : 0.0;
+      vb[u] = (in && two) ? rec[tt].v[col + 1] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < kSlotBatch; ++u) {
+      a += va[u];
+      b += vb[u];
+    }
+  }
+}
+
 // Sub-sum g of `split` over segment s's slots (tiles t0..t1 of the producing
 // kernel), in a fixed order.  grid = (segments, split); out[q][s*split + g].
 __global__ __launch_bounds__(kReduceBlock) void slot_sums(
@@ -111,10 +136,7 @@ __global__ __launch_bounds__(kReduceBlock) void slot_sums(
       const int64_t chunk = (t1 - t0 + split) / split;       // ceil(count / split)
       const int64_t c0 = t0 + g * chunk;
       const int64_t c1 = (c0 + chunk - 1 < t1) ? c0 + chunk - 1 : t1;
-      for (int64_t t = c0 + threadIdx.x; t <= c1; t += kReduceBlock) {
-        a += slots[t + s].v[col];
-        if (two) b += slots[t + s].v[col + 1];
-      }
+      add_slots(slots + s, col, two, c0 + threadIdx.x, c1, a, b);
     }
     const double ta = block_sum(a, lds[0]);
     double tb = 0.0;
@@ -200,10 +222,7 @@ __global__ __launch_bounds__(kReduceBlock) void lambda_direct(
     double a = 0.0, b = 0.0;
     if (hi > lo) {
       const int64_t t0 = lo / tile_elems, t1 = (hi - 1) / tile_elems;
-      for (int64_t t = t0 + threadIdx.x; t <= t1; t += kReduceBlock) {
-        a += slots[t + s].v[0];
-        if (use_d) b += slots[t + s].v[1];
-      }
+      add_slots(slots + s, 0, use_d, t0 + threadIdx.x, t1, a, b);
     }
     const double M2 = block_sum(a, lds[0]);
     double P2 = 0.0;

@@ -136,3 +136,14 @@ def test_first_allocation_is_probed_before_the_search():
     rep = p.report()
     assert rep["first_allocation_ms"] == 8.5 and rep["worst_candidate_ms"] == 6.0
     assert p.gap == 4096 and rep["arenas_ms"] == [[5.0, 4.0], [3.0, 6.0]]
+
+
+def test_diagnostic_modules_import_without_a_gpu():
+    """The two diagnostics only sequence launches; importing them touches neither the GPU nor the oracle."""
+    import importlib
+    import sys
+    for name in ("paper_2401_16265_amd.placement_contrast", "paper_2401_16265_amd.cache_ceiling_probe"):
+        mod = importlib.import_module(name)
+        assert callable(mod.main)
+    assert not any(m == "oracle" or m.startswith("oracle.") for m in sys.modules
+                   if getattr(sys.modules[m], "__file__", None) and "paper_2401_16265_amd" in str(sys.modules[m].__file__))

@@ -139,11 +139,11 @@ def test_first_allocation_is_probed_before_the_search():
 
 
 def test_diagnostic_modules_import_without_a_gpu():
-    """The two diagnostics only sequence launches; importing them touches neither the GPU nor the oracle."""
+    """The two diagnostics only sequence launches: importing them needs no GPU, and their source
+    names nothing under oracle/."""
     import importlib
-    import sys
+    import inspect
     for name in ("paper_2401_16265_amd.placement_contrast", "paper_2401_16265_amd.cache_ceiling_probe"):
         mod = importlib.import_module(name)
         assert callable(mod.main)
-    assert not any(m == "oracle" or m.startswith("oracle.") for m in sys.modules
-                   if getattr(sys.modules[m], "__file__", None) and "paper_2401_16265_amd" in str(sys.modules[m].__file__))
+        assert "oracle" not in inspect.getsource(mod)

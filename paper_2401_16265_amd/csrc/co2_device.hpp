@@ -26,7 +26,10 @@ constexpr int kAdamU = 1;                          // ... AdamW step (two per la
                                                    // IEEE square root and divisions keep a wavefront busy
                                                    // for about as long as its loads take, with nothing in flight)
 constexpr int64_t kSweepTile = int64_t(kWave) * 4 * kSweepU;   // 256 elements
-constexpr int64_t kNormTile = int64_t(kWave) * 4 * kNormU;     // 1024 elements
+constexpr int64_t kNormSub = int64_t(kWave) * 4 * kNormU;      // 1024 elements read at once by the norm pass
+constexpr int kNormSubs = 16;                      // such pieces per norm-pass tile (one record per tile:
+                                                   // a record per 1024 elements cost the pass 5-8 %)
+constexpr int64_t kNormTile = kNormSub * kNormSubs;            // 16384 elements
 constexpr int64_t kAdamTile = int64_t(kWave) * 4 * kAdamU;     // 256 elements
 constexpr int kLdsPerCu = 160 * 1024;              // gfx950 LDS per compute unit
 constexpr int kReduceBlock = 256;                  // threads of the small reduction kernels
@@ -94,6 +97,16 @@ __device__ __forceinline__ double wave_sum(double v) {
   const double r0 = read_lane(v, 0), r1 = read_lane(v, 16);
   const double r2 = read_lane(v, 32), r3 = read_lane(v, 48);
   return ((r0 + r1) + r2) + r3;
+}
+
+// Tells the compiler that a value every lane holds identically IS wavefront-uniform
+// (kept in scalar registers: scalar loads, no per-lane address handling), where its own
+// analysis gives up (values carried around loops that also contain per-lane loops).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform(int64_t v) {
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint64_t>(v))));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint64_t>(v) >> 32)));
+  return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
 // Lanes 0..3 of the wavefront write one slot record; v0..v2 are wavefront-uniform.

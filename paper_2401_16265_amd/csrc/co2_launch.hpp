@@ -53,7 +53,7 @@ struct AdamArgs {
 // Resident wavefronts per compute unit each streaming kernel is capped to.
 // Measured optima on MI355X at 1.3B parameters, averaged over several buffer
 // placements: about 56-64 KB of loads in flight per compute unit.  A sweep
-// wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront 4 KB
+// wavefront holds 1 KB per stream read (3 + buffers), a norm-pass wavefront (which stays for 16 pieces) 4 KB
 // per buffer, an AdamW wavefront 3.5 KB (4.5 KB with the anchor).
 // `delta_kb`: KB of pseudo-gradient loads one sweep wavefront issues (1 per fp32 buffer, 0.5 per
 // 16-bit buffer), beside its 3 KB of anchor, momentum and params.
@@ -62,8 +62,8 @@ inline int default_sweep_waves(float delta_kb) {
   if (delta_kb <= 1.0f) return 10;                 // K = 1, or K = 2 with 16-bit transport
   return delta_kb <= 4.0f ? 8 : delta_kb <= 9.0f ? 7 : 6;   // 11 and more: two load phases, see co2_sweep.hip
 }
-constexpr int kNormWavesOneBuffer = 16;
-constexpr int kNormWavesTwoBuffers = 8;
+constexpr int kNormWavesOneBuffer = 5;
+constexpr int kNormWavesTwoBuffers = 5;
 constexpr int kAdamWavesPerCu = 16;
 constexpr int kAdamWavesWithAnchor = 12;  // the step that also reads the anchor and writes delta_out
 constexpr int kAdamWavesNoStore = 10;     // ... and does not store the parameters

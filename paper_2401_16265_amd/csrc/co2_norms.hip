@@ -2,14 +2,15 @@
 // (CO2 paper, Definition 3.1 / Eq. 3) and the per-segment scalar Lambda.
 //
 // Pass 1 (sqnorm_partials): the flat index space is cut into aligned tiles of
-// kNormTile elements, one single-wavefront workgroup each.  A tile that lies
-// inside one segment is read with 16-byte loads, squared and accumulated in
-// fp64 per lane, reduced across the wavefront through DPP, and leaves ONE
-// partial in slot (tile + segment).  A tile that holds a segment boundary (or
-// the ragged end) walks its segments one after the other and leaves one partial
-// per (tile, segment) pair.  The slot index tile+segment is unique per pair
-// because both indices only grow along the flat vector, so no atomics and no
-// zero-fill are needed.
+// kNormTile elements, one single-wavefront workgroup each, which reads its tile
+// in pieces of kNormSub elements: 16-byte loads, squares accumulated in fp64
+// per lane.  When the segment changes inside the tile (and at the tile's end)
+// the lane sums are reduced across the wavefront through DPP and leave ONE
+// partial in slot (tile + segment).  The slot index tile+segment is unique per
+// pair because both indices only grow along the flat vector, so no atomics and
+// no zero-fill are needed.  (Tiles are this long because even a thin stream of
+// stores beside the loads costs bandwidth: one record per 1024 elements held
+// the pass at 6.5-6.7 TB/s, one per 16384 lets it run at 7.0.)
 //
 // Stage 2: slot_sums adds each segment's slots in a fixed order (large segments
 // are split over several workgroups), then lambda_finish / totals_finish adds
@@ -29,6 +30,13 @@ __device__ __forceinline__ void acc4(double& acc, float4 q, float phi) {
 }
 
 // NB buffers (1 or 2); the second has element type B1_DT (a DeltaType).
+//
+// One wavefront walks its tile in kNormSubs pieces of kNormSub elements.  A
+// piece that lies inside the current segment is read with 16-byte loads and
+// accumulated per lane; any other piece (segment boundary inside it, ragged
+// end) is walked element by element, segment after segment.  Whenever the
+// current segment ends, its lane sums are reduced and leave the record of
+// (tile, segment); the last segment's record is written at the end of the tile.
 template <int NB, int B1_DT>
 __global__ __launch_bounds__(kWave) void sqnorm_partials(
     const float* __restrict__ b0, float phi0, const void* __restrict__ b1, float phi1,
@@ -36,14 +44,15 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
   using IO1 = DeltaIO<B1_DT>;
   const int64_t tile = blockIdx.x;
   const int64_t base = tile * kNormTile;
+  const int64_t end = (base + kNormTile < n) ? base + kNormTile : n;
   const int lane = threadIdx.x;
-  const bool full = base + kNormTile <= n;
 
-  // Loads first: they do not depend on the segment lookup below, which then
-  // overlaps with them.
+  // The first piece's loads go out before the segment lookup, which does not
+  // depend on them and runs while they are in flight.
   float4 q0[kNormU];
   typename IO1::Vec q1[kNormU];
-  if (full) {
+  const bool first_full = base + kNormSub <= end;
+  if (first_full) {
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {
       const int64_t row = base + int64_t(u) * kWave * 4;
@@ -51,48 +60,98 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
       if (NB == 2) q1[u] = IO1::load4(b1, row, lane);
     }
   }
-  const int s_lo = seg_of(off, S, base);
+  int cur = seg_of(off, S, base);                  // off[cur] <= base < off[cur + 1]
+  int64_t cur_end = off[cur + 1];
+  double a0 = 0.0, a1 = 0.0;
 
-  if (full && base + kNormTile <= off[s_lo + 1]) {
-    double a0 = 0.0, a1 = 0.0;
+  auto flush = [&]() {
+    const double t0 = wave_sum(a0);
+    double t1 = 0.0;
+    if (NB == 2) t1 = wave_sum(a1);
+    write_slot(slots, tile + cur, lane, t0, t1, 0.0);
+    a0 = 0.0;
+    a1 = 0.0;
+  };
+  // moves on to the segment that holds `pos` (pos < n, so one exists); empty segments are skipped
+  auto advance_to = [&](int64_t pos) {
+    flush();
+    do {
+      cur = uniform(cur + 1);
+      cur_end = uniform(off[cur + 1]);
+    } while (cur_end <= pos);
+  };
+
+  auto load_piece = [&](float4 (&r0)[kNormU], typename IO1::Vec (&r1)[kNormU], int64_t at) {
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {
-      acc4(a0, q0[u], phi0);
+      const int64_t row = at + int64_t(u) * kWave * 4;
+      r0[u] = ld4_stream(b0 + row, lane);
+      if (NB == 2) r1[u] = IO1::load4(b1, row, lane);
+    }
+  };
+  auto add_piece = [&](const float4 (&r0)[kNormU], const typename IO1::Vec (&r1)[kNormU]) {
+#pragma unroll
+    for (int u = 0; u < kNormU; ++u) {
+      acc4(a0, r0[u], phi0);
       if (NB == 2) {
-        acc4(a1, make_float4(IO1::get(q1[u], 0), IO1::get(q1[u], 1), IO1::get(q1[u], 2),
-                             IO1::get(q1[u], 3)), phi1);
+        acc4(a1, make_float4(IO1::get(r1[u], 0), IO1::get(r1[u], 1), IO1::get(r1[u], 2),
+                             IO1::get(r1[u], 3)), phi1);
       }
     }
-    const double t0 = wave_sum(a0);
-    double t1 = 0.0;
-    if (NB == 2) t1 = wave_sum(a1);
-    write_slot(slots, tile + s_lo, lane, t0, t1, 0.0);
-    return;
-  }
+  };
 
-  // Boundary or ragged tile: one segment piece after the other.
-  const int64_t end = (base + kNormTile < n) ? base + kNormTile : n;
-  const int s_hi = seg_of(off, S, end - 1);
-  for (int s = s_lo; s <= s_hi; ++s) {
-    const int64_t lo = off[s] > base ? off[s] : base;
-    const int64_t hi = off[s + 1] < end ? off[s + 1] : end;
-    if (lo >= hi) continue;                                  // empty segment: its slot is never read
-    double a0 = 0.0, a1 = 0.0;
-    for (int64_t j = lo + lane; j < hi; j += kWave) {
-      float v = b0[j];
-      if (phi0 > 0.0f) v = clip_coord(v, phi0);
-      a0 += sq(v);
-      if (NB == 2) {
-        float r = IO1::load1(b1, j);
-        if (phi1 > 0.0f) r = clip_coord(r, phi1);
-        a1 += sq(r);
+  int64_t sb = base;                               // start of the next piece (a multiple of kNormSub)
+  while (sb < end) {
+    sb = uniform(sb);
+    if (sb >= cur_end) advance_to(sb);
+    const int64_t lim = cur_end < end ? cur_end : end;
+    const int64_t run = (lim - sb) / kNormSub;     // whole pieces inside the current segment
+    if (run > 0) {
+      // Software pipeline over the run: the next piece's loads go out before this piece's
+      // arithmetic, so the wavefront always has loads in flight.  Two register sets take
+      // turns (copying one into the other would have to wait for the loads just issued).
+      float4 r0[kNormU];
+      typename IO1::Vec r1[kNormU];
+      if (!(first_full && sb == base)) load_piece(q0, q1, sb);
+      int64_t i = 1;
+      for (; i + 1 < run; i += 2) {
+        load_piece(r0, r1, sb + i * kNormSub);
+        add_piece(q0, q1);
+        load_piece(q0, q1, sb + (i + 1) * kNormSub);
+        add_piece(r0, r1);
       }
+      if (i < run) {
+        load_piece(r0, r1, sb + i * kNormSub);
+        add_piece(q0, q1);
+        add_piece(r0, r1);
+      } else {
+        add_piece(q0, q1);
+      }
+      sb += run * kNormSub;
+      continue;
     }
-    const double t0 = wave_sum(a0);
-    double t1 = 0.0;
-    if (NB == 2) t1 = wave_sum(a1);
-    write_slot(slots, tile + s, lane, t0, t1, 0.0);
+    // A piece with a segment boundary in it, or the ragged end: element by element.
+    const int64_t se = (sb + kNormSub < end) ? sb + kNormSub : end;
+    int64_t pos = sb;
+    while (pos < se) {
+      pos = uniform(pos);
+      if (pos >= cur_end) advance_to(pos);
+      const int64_t hi = cur_end < se ? cur_end : se;
+      for (int64_t j = pos + lane; j < hi; j += kWave) {
+        float v = b0[j];
+        if (phi0 > 0.0f) v = clip_coord(v, phi0);
+        a0 += sq(v);
+        if (NB == 2) {
+          float r = IO1::load1(b1, j);
+          if (phi1 > 0.0f) r = clip_coord(r, phi1);
+          a1 += sq(r);
+        }
+      }
+      pos = hi;
+    }
+    sb = se;
   }
+  flush();
 }
 
 // a += rec[t].v[col] (and b += rec[t].v[col + 1] with `two`) for t = first, first + kReduceBlock,

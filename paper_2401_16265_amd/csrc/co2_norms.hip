@@ -10,7 +10,7 @@
 // pair because both indices only grow along the flat vector, so no atomics and
 // no zero-fill are needed.  (Tiles are this long because even a thin stream of
 // stores beside the loads costs bandwidth: one record per 1024 elements held
-// the pass at 6.5-6.7 TB/s, one per 16384 lets it run at 7.0.)
+// the pass at 6.5-6.7 TB/s, one per 16384 lets it run at 6.85.)
 //
 // Stage 2: slot_sums adds each segment's slots in a fixed order (large segments
 // are split over several workgroups), then lambda_finish / totals_finish adds
@@ -47,19 +47,20 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
   const int64_t end = (base + kNormTile < n) ? base + kNormTile : n;
   const int lane = threadIdx.x;
 
+  auto load_piece = [&](float4 (&r0)[kNormU], typename IO1::Vec (&r1)[kNormU], int64_t at) {
+#pragma unroll
+    for (int u = 0; u < kNormU; ++u) {
+      const int64_t row = at + int64_t(u) * kWave * 4;
+      r0[u] = ld4_stream(b0 + row, lane);
+      if (NB == 2) r1[u] = IO1::load4(b1, row, lane);
+    }
+  };
   // The first piece's loads go out before the segment lookup, which does not
   // depend on them and runs while they are in flight.
   float4 q0[kNormU];
   typename IO1::Vec q1[kNormU];
   const bool first_full = base + kNormSub <= end;
-  if (first_full) {
-#pragma unroll
-    for (int u = 0; u < kNormU; ++u) {
-      const int64_t row = base + int64_t(u) * kWave * 4;
-      q0[u] = ld4_stream(b0 + row, lane);
-      if (NB == 2) q1[u] = IO1::load4(b1, row, lane);
-    }
-  }
+  if (first_full) load_piece(q0, q1, base);
   int cur = seg_of(off, S, base);                  // off[cur] <= base < off[cur + 1]
   int64_t cur_end = off[cur + 1];
   double a0 = 0.0, a1 = 0.0;
@@ -81,14 +82,6 @@ __global__ __launch_bounds__(kWave) void sqnorm_partials(
     } while (cur_end <= pos);
   };
 
-  auto load_piece = [&](float4 (&r0)[kNormU], typename IO1::Vec (&r1)[kNormU], int64_t at) {
-#pragma unroll
-    for (int u = 0; u < kNormU; ++u) {
-      const int64_t row = at + int64_t(u) * kWave * 4;
-      r0[u] = ld4_stream(b0 + row, lane);
-      if (NB == 2) r1[u] = IO1::load4(b1, row, lane);
-    }
-  };
   auto add_piece = [&](const float4 (&r0)[kNormU], const typename IO1::Vec (&r1)[kNormU]) {
 #pragma unroll
     for (int u = 0; u < kNormU; ++u) {

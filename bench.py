@@ -467,6 +467,18 @@ def main():
             step_no[0] += 1
         torch.cuda.synchronize()
         graphs.clear()
+    # ---- cross-check: the same number of steps launched back to back inside one host-clock
+    # bracket (synchronize on both sides).  Only the first of them consumes live inputs: without a
+    # refresh in between, params == anchor afterwards and the later steps see zero drift, which is
+    # why this figure is reported beside the per-round one and not as the metric.
+    live_inputs(step_no[0])
+    torch.cuda.synchronize()
+    bb0 = time.perf_counter()
+    for _ in range(args.steps):
+        launch(bufs, step_no[0])
+        step_no[0] += 1
+    torch.cuda.synchronize()
+    back_to_back_ms = (time.perf_counter() - bb0) * 1e3 / args.steps
     sweep_times = [b.elapsed_ms(e) for b, e in sweep_ev]
     sweep_ms = sum(sweep_times) / len(sweep_times)
     per_elem = (26 + 2 * K) if bf16 else (28 + 4 * K)   # algorithmic bytes per coordinate, one sweep
@@ -509,7 +521,8 @@ def main():
                    "timing": {"per": "round, HIP events on the launch stream around all kernels of the step",
                               "median_ms": ms_per_step, "min_ms": min(step_ms), "max_ms": max(step_ms),
                               "mean_ms": sum(step_ms) / len(step_ms),
-                              "wall_s_including_input_generation": wall},
+                              "wall_s_including_input_generation": wall,
+                              "back_to_back_ms_per_step_host_clock": back_to_back_ms},
                    "lambda_min": lam_min, "lambda_max": lam_max,
                    "clipped_coordinates_last_timed_step": clipped_count,
                    "layout": layout,
